@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the local-share hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+an AllReduce of the 8 x 256 MiB bf16 message (configuration 2) followed by an
+AllGather of 8 x 32 MiB bf16 slices into 256 MiB (configuration 1), both through
+the C ABI with the two-path split chosen by the tuned, adaptive balancer
+(partition -> device path + host-staged path -> join -> evaluate/rebalance).
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
+timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
+dominant kernel (the N-way reduce) against the 8 TB/s HBM3E peak from per-launch
+HIP-event timings taken inside the timed region; `cpu_baseline` is the CPU
+oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "AllReduce/AllGather local-share GB/s at 256MB (8 sim ranks); % HBM peak"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def median(v):
+    v = sorted(v)
+    n = len(v)
+    return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
+
+
+def read_traffic_note():
+    """HBM traffic per launch of the reduce kernel, from the committed rocprofv3
+    counter summary (bytes, scaled by the copy-kernel calibration), or None."""
+    path = os.path.join(ROOT, "profiles", "reduce_n_allreduce_bf16_256MiB_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(oc, wl, ar_host, ag_host, ar_bytes, ag_bytes, passes=3):
+    threads = oc.get_threads()
+    oc.allreduce(ar_host)          # warm pass (page faults, thread pool)
+    oc.allgather(ag_host)
+    best = None
+    for _ in range(passes):
+        t0 = time.perf_counter()
+        oc.allreduce(ar_host)
+        oc.allgather(ag_host)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return {"value": (ar_bytes + ag_bytes) / best / 1e9, "unit": "GB/s", "cores": threads,
+            "kind": "oracle", "seconds_per_step": best,
+            "sample": "the full step (configuration 2 AllReduce + configuration 1 AllGather), same bytes as "
+                      "the GPU run; best of %d passes after one warm pass, %d OpenMP threads" % (passes, threads)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--mode", default="adaptive",
+                    help="adaptive (tuned balancer) | device (host share 0) | static:UNITS (of 10000)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed device-only / static-split legs")
+    ap.add_argument("--reduce-threads", type=int, default=0)
+    ap.add_argument("--reduce-unroll", type=int, default=0)
+    ap.add_argument("--reduce-waves", type=int, default=0)
+    ap.add_argument("--copy-threads", type=int, default=0)
+    ap.add_argument("--copy-unroll", type=int, default=0)
+    ap.add_argument("--copy-waves", type=int, default=0)
+    ap.add_argument("--nontemporal", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is the single-GPU local share; it runs on exactly one GPU "
+                 "(--gpus 1). No figure at several GPUs exists.")
+
+    import torch
+    from paper_2510_15882_amd import binding as fx
+    from paper_2510_15882_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    fx.lib()
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w_ar, w_ag = wl.config(2), wl.config(1)
+    N = 8
+    log("generating inputs on the GPU ...")
+    ar_bufs = wl.make_rank_buffers(w_ar, dev)
+    ag_slices = wl.make_rank_buffers(w_ag, dev)
+    ar_out = torch.empty(w_ar.count, dtype=w_ar.dtype, device=dev)
+    ag_out = torch.empty(N * w_ag.count, dtype=w_ag.dtype, device=dev)
+    ar_bytes = (N + 1) * w_ar.bytes_per_rank
+    ag_bytes = 2 * N * w_ag.bytes_per_rank
+
+    cfg = fx.flex_config_default()
+    cfg.reduce_threads, cfg.reduce_unroll, cfg.reduce_waves_per_cu = args.reduce_threads, args.reduce_unroll, args.reduce_waves
+    cfg.copy_threads, cfg.copy_unroll, cfg.copy_waves_per_cu = args.copy_threads, args.copy_unroll, args.copy_waves
+    cfg.nontemporal = args.nontemporal
+    comm = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def ar():
+        fx.flex_allreduce_local(comm, ar_bufs, ar_out, stream=stream)
+
+    def ag():
+        fx.flex_allgather_local(comm, ag_slices, ag_out, stream=stream)
+
+    def timed_calls(fn, n):
+        """Median per-call milliseconds of n calls, HIP events on the launch stream."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        with torch.cuda.stream(stream):
+            for a, b in evs:
+                a.record(stream)
+                fn()
+                b.record(stream)
+        stream.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+
+    extras = {}
+    tune = {}
+    with torch.cuda.stream(stream):
+        # ---- untimed: Stage 1 of the balancer, or a fixed split ----------
+        if args.mode == "adaptive":
+            for coll, bufs, out, name in ((fx.FLEX_ALLREDUCE, ar_bufs, ar_out, "allreduce"),
+                                          (fx.FLEX_ALLGATHER, ag_slices, ag_out, "allgather")):
+                res = fx.flex_comm_tune(comm, coll, bufs, out, stream=stream)
+                tune[name] = {"path_bw_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
+                              "initial_shares": list(res.initial_shares)[:2], "shares": list(res.shares)[:2],
+                              "iterations": res.iterations, "active_mask": res.active_mask}
+                log("tuned", name, tune[name])
+                fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
+        elif args.mode == "device":
+            pass
+        elif args.mode.startswith("static:"):
+            units = int(args.mode.split(":")[1])
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+            fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+        else:
+            sys.exit("unknown --mode")
+
+        for _ in range(args.warmup):
+            ar()
+            ag()
+    stream.synchronize()
+    fx.flex_evaluator_drain(comm)
+    s_ar0 = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
+
+    # ---- timed region: exactly --steps steps --------------------------------
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for k in range(args.steps):
+            ev[k][0].record(stream)
+            ar()
+            ev[k][1].record(stream)
+            ag()
+            ev[k][2].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    fx.flex_evaluator_drain(comm)
+    s_ar1 = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
+    s_ag1 = fx.flex_get_stats(comm, fx.FLEX_ALLGATHER, w_ag.count, w_ag.dtype)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = (ar_bytes + ag_bytes) / (ms_per_step * 1e-3) / 1e9
+    ar_ms = [e[0].elapsed_time(e[1]) for e in ev]
+    ag_ms = [e[1].elapsed_time(e[2]) for e in ev]
+
+    # Dominant kernel: the N-way reduce of the device part.  When the call was
+    # split, its launch is bracketed by the Evaluator's own events (fork ->
+    # device path done) on the same stream; otherwise by the events above.
+    split_samples = s_ar1.samples - s_ar0.samples
+    dev_elems = s_ar1.last_split if s_ar1.last_count == w_ar.count else w_ar.count
+    if split_samples > 0:
+        total_dev_s = s_ar1.mean_time_s[0] * s_ar1.samples - s_ar0.mean_time_s[0] * s_ar0.samples
+        kern_ms = total_dev_s / split_samples * 1e3
+        how = "Evaluator events fork->device-path-done, mean of %d split calls" % split_samples
+    else:
+        kern_ms = sum(ar_ms) / len(ar_ms)
+        how = "HIP events around each launch on the launch stream, mean of %d" % len(ar_ms)
+    bytes_per_elem = (N + 1) * 2
+    achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "reduce_n_kernel<8, bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note(),
+                "launch_ms": kern_ms, "elements_per_launch": int(dev_elems), "bytes_per_element": bytes_per_elem,
+                "timing": how}
+
+    result = {
+        "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[2] AllReduce bf16 8 ranks x 256 MiB (fp32 accumulate) + configs[1] "
+                               "AllGather bf16 8 x 32 MiB -> 256 MiB, one call each per step",
+                   "mode": args.mode, "nranks": N, "algorithmic_bytes_per_step": ar_bytes + ag_bytes,
+                   "launch": {k: getattr(cfg, k) for k in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu",
+                                                            "copy_threads", "copy_unroll", "copy_waves_per_cu",
+                                                            "nontemporal")}},
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "allreduce": {"ms_median": median(ar_ms), "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,
+                      "algbw_GBs": w_ar.bytes_per_rank / (median(ar_ms) * 1e-3) / 1e9,
+                      "host_units": int(s_ar1.balancer.shares[1]) if args.mode == "adaptive" else s_ar1.static_host_units,
+                      "split_calls_timed": int(split_samples)},
+        "allgather": {"ms_median": median(ag_ms), "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
+                      "algbw_GBs": N * w_ag.bytes_per_rank / (median(ag_ms) * 1e-3) / 1e9,
+                      "host_units": int(s_ag1.balancer.shares[1]) if args.mode == "adaptive" else s_ag1.static_host_units},
+    }
+    if tune:
+        result["tune"] = tune
+
+    # ---- untimed extras: device-only and the static split sweep -------------
+    if not args.no_extras:
+        for coll in (fx.FLEX_ALLREDUCE, fx.FLEX_ALLGATHER):
+            fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_STATIC, 0)
+        d_ar = median(timed_calls(ar, 50))
+        d_ag = median(timed_calls(ag, 50))
+        extras["device_only"] = {"allreduce_ms": d_ar, "allreduce_hbm_GBs": ar_bytes / d_ar / 1e6,
+                                 "allgather_ms": d_ag, "allgather_hbm_GBs": ag_bytes / d_ag / 1e6}
+        sweep = {}
+        for units in (100, 500, 1200, 2200):
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+            ms = median(timed_calls(ar, 10))
+            fx.flex_evaluator_drain(comm)
+            st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
+            host_elems = st.last_count - st.last_split
+            pcie_bytes = (N - 1) * host_elems * 2          # each direction
+            sweep[str(units)] = {"allreduce_ms": ms, "hbm_GBs": ar_bytes / ms / 1e6,
+                                 "device_path_ms": st.last_time_s[0] * 1e3, "host_path_ms": st.last_time_s[1] * 1e3,
+                                 "pcie_GBs_per_direction": pcie_bytes / st.last_time_s[1] / 1e9 if st.last_time_s[1] > 0 else None}
+        extras["allreduce_static_split"] = sweep
+        result["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        from oracle import collectives as oc
+        log("timing the CPU oracle ...")
+        ar_host = [wl.to_numpy_bits(b) for b in ar_bufs]
+        ag_host = [wl.to_numpy_bits(b) for b in ag_slices]
+        result["cpu_baseline"] = cpu_baseline(oc, wl, ar_host, ag_host, ar_bytes, ag_bytes)
+
+    torch.cuda.synchronize()
+    fx.flex_comm_destroy(comm)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,322 @@
+/*
+ * flexlink.h - C ABI of the MI355X-native local share of FlexLink's collectives.
+ *
+ * FlexLink (arXiv 2510.15882) splits every AllReduce / AllGather message over
+ * several heterogeneous paths in proportion to a share vector and keeps that
+ * vector balanced with a two-stage load balancer (paper: Design; Section
+ * "Communicator"; Section "Two-Stage Load Balancing Strategy"; Algorithm 1).
+ *
+ * This library builds the part of that which one GPU can show.  The N ranks'
+ * contributions are N buffers resident in one GPU's HBM.  Two paths exist:
+ *
+ *   FLEX_PATH_DEVICE  the on-device path (HIP kernels reading the rank buffers
+ *                     straight from HBM); it plays the role the paper gives to
+ *                     NVLink, i.e. it is the primary path the balancer favours;
+ *   FLEX_PATH_HOST    the host-staged path of Section "Communicator": peer
+ *                     data goes device -> pinned host buffer -> device through
+ *                     a double-buffered pipeline on side streams.
+ *
+ * General conventions
+ *   - Every function returns a flex_status code (0 = FLEX_OK) unless stated
+ *     otherwise, never throws and never aborts.  After a non-zero return,
+ *     flex_last_error() gives a message for the calling thread.
+ *   - "device pointer" = address in the HBM of the current HIP device;
+ *     "host pointer" = ordinary process memory.  Each argument says which.
+ *   - The caller owns every buffer it passes in.  The library owns what a
+ *     flex_comm_t holds: pinned transit buffers, device scratch, side streams,
+ *     events, balancer state.
+ *   - Collective calls are asynchronous: they enqueue work on the caller's HIP
+ *     stream (side streams fork from it and join back into it by events) and
+ *     return.  Stream order is the only synchronisation the caller sees; any
+ *     number of calls may be queued back to back on one stream.
+ *   - A flex_comm_t is bound to the HIP device that was current at creation
+ *     and is not thread-safe; use one per thread/stream.
+ *   - Structs are plain C with fixed-width fields; obtain defaults with the
+ *     *_default() call and then change fields.
+ */
+#ifndef FLEXLINK_H
+#define FLEXLINK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLEX_MAX_RANKS 8
+#define FLEX_MAX_PATHS 4
+
+typedef struct flex_comm flex_comm_t;         /* opaque; device-bound */
+typedef struct flex_balancer flex_balancer_t; /* opaque; pure host state */
+
+enum flex_status {
+    FLEX_OK = 0,
+    FLEX_ERR_INVALID_ARG = 1, /* null pointer, size or index out of range; nothing was enqueued */
+    FLEX_ERR_UNSUPPORTED = 2, /* unknown dtype / op / collective; nothing was enqueued */
+    FLEX_ERR_HIP = 3,         /* a HIP runtime call failed; see flex_last_error() */
+    FLEX_ERR_NOMEM = 4,       /* host or device allocation failed */
+    FLEX_ERR_STATE = 5        /* call not valid in the object's current state */
+};
+
+enum flex_dtype { FLEX_F32 = 0, FLEX_BF16 = 1 };
+enum flex_op { FLEX_SUM = 0 };
+enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1 };
+enum flex_path { FLEX_PATH_DEVICE = 0, FLEX_PATH_HOST = 1 };
+enum flex_split_mode { FLEX_SPLIT_STATIC = 0, FLEX_SPLIT_ADAPTIVE = 1 };
+enum flex_balancer_stage { FLEX_STAGE_TUNING = 1, FLEX_STAGE_RUNTIME = 2 };
+
+/* ------------------------------------------------------------------------
+ * Load balancer (paper: Section "Two-Stage Load Balancing Strategy",
+ * Algorithm 1 for Stage 1, Section "Stage 2: Runtime Fine-Grained Adjustment"
+ * for Stage 2).  Pure host code: no HIP call is made by any flex_balancer_*
+ * function, so they work on a machine without a GPU.
+ *
+ * Shares are non-negative integers summing to share_total.  Path 0 is the
+ * primary path (NVLink in the paper, the device path here).
+ * ---------------------------------------------------------------------- */
+typedef struct flex_balancer_cfg {
+    uint32_t share_total;          /* units the message is divided into (default 10000) */
+    uint32_t initial_step;         /* Algorithm 1 INITIAL_ADJUSTMENT_STEP, in units (default 64) */
+    uint32_t stability_required;   /* Algorithm 1 STABILITY_REQUIRED (default 3) */
+    uint32_t max_tune_iters;       /* Algorithm 1 loop bound (paper: 100) */
+    uint32_t window;               /* Stage 2: calls per Evaluator window = Load Balancer period (default 10) */
+    uint32_t runtime_step;         /* Stage 2: fixed share moved per adjustment, in units (default 4) */
+    double convergence_threshold;  /* Algorithm 1 CONVERGENCE_THRESHOLD on (Tslow-Tfast)/Tfast (default 0.05) */
+    double runtime_threshold;      /* Stage 2 threshold on the same ratio of window medians (default 0.10) */
+} flex_balancer_cfg_t;
+
+typedef struct flex_balancer_state {
+    uint32_t npaths;
+    uint32_t stage;                /* flex_balancer_stage */
+    uint32_t tune_iters;           /* Algorithm 1 iterations measured so far */
+    uint32_t step;                 /* current Algorithm 1 step */
+    uint32_t stability_count;
+    int32_t prev_slowest;          /* -1 = none yet */
+    uint32_t active_mask;          /* bit p set = path p active */
+    uint32_t window_fill;          /* Stage 2 samples held in the current window */
+    uint64_t adjustments;          /* Stage 2 moves made so far */
+    uint32_t shares[FLEX_MAX_PATHS];
+} flex_balancer_state_t;
+
+/* Fill *cfg (host pointer) with the defaults listed above. */
+int flex_balancer_cfg_default(flex_balancer_cfg_t* cfg);
+
+/* Create a balancer in Stage 1 with bandwidth-proportional starting shares
+ * (the paper's InitializeShares, "NVLink gets dominant share").
+ *   b        host pointer; receives the new object (caller destroys it).
+ *   npaths   1..FLEX_MAX_PATHS.
+ *   path_bw  host array of npaths rates, same unit for all: how fast path p
+ *            moves a whole message on its own; <= 0 marks a path unavailable.
+ *            Every path p >= 1 gets floor(total * bw[p] / sum(bw)) units, path 0
+ *            the rest; a path with 0 units starts inactive.
+ *   cfg      host pointer or NULL for defaults.
+ * Errors: INVALID_ARG (null b/path_bw, npaths out of range, bw[0] <= 0,
+ * non-finite rates, zero share_total/window/initial_step), NOMEM. */
+int flex_balancer_init(flex_balancer_t** b, int npaths, const double* path_bw,
+                       const flex_balancer_cfg_t* cfg);
+
+/* Same, but start from explicit shares (host array of npaths units that must
+ * sum to cfg->share_total). */
+int flex_balancer_init_shares(flex_balancer_t** b, int npaths, const uint32_t* shares,
+                              const flex_balancer_cfg_t* cfg);
+
+/* Feed one measurement of per-path completion times and get the shares to use
+ * next.
+ *   path_time_s  host array of npaths seconds; entries of inactive paths are
+ *                ignored; every active path must report a finite time > 0.
+ *   shares_out   host array of npaths units, may be NULL.
+ * In Stage 1 one call is one iteration of Algorithm 1's loop body (find slowest
+ * and fastest active path, test the imbalance, move `step` units from the
+ * slowest path to the primary path, or from a bottlenecked primary path to the
+ * fastest one, halve the step when the bottleneck moved, deactivate a drained
+ * path).  When the loop's exit condition holds (stable for stability_required
+ * iterations, only the primary path left, or max_tune_iters reached) the
+ * balancer moves to Stage 2.  In Stage 2 each call adds a sample to the
+ * Evaluator window; the call that fills the window compares the window medians
+ * and moves at most runtime_step units by the same source/target rule.
+ * Errors: INVALID_ARG (null, bad time for an active path): state unchanged. */
+int flex_balancer_update(flex_balancer_t* b, const double* path_time_s, uint32_t* shares_out);
+
+/* End Stage 1 now (no-op in Stage 2): later updates are Stage-2 samples. */
+int flex_balancer_finish_tuning(flex_balancer_t* b);
+
+/* Copy the balancer's state to *out (host pointer). */
+int flex_balancer_get(const flex_balancer_t* b, flex_balancer_state_t* out);
+
+/* Free the object.  NULL is accepted. */
+int flex_balancer_destroy(flex_balancer_t* b);
+
+/* ------------------------------------------------------------------------
+ * Message partition (paper: Design - the Communicator divides each payload
+ * over the paths according to the shares and runs them concurrently).
+ *
+ * Computes the cut between the device part [0, split) and the host part
+ * [split, count) of a message of `count` elements for a host share of
+ * host_units / share_total:  the host part is owed floor(count*host_units/
+ * share_total) elements; the cut is rounded down to a multiple of align_elems
+ * (so the host part only grows by rounding, and the ragged end of the message
+ * belongs to it); host_units == 0, count < min_count or count < align_elems
+ * gives split == count; host_units == share_total gives split == 0; a non-zero
+ * share never yields an empty host part.  Pure host arithmetic.
+ * Errors: INVALID_ARG (null split_out, host_units > share_total, zero
+ * share_total or align_elems). */
+int flex_partition(uint64_t count, uint32_t host_units, uint32_t share_total,
+                   uint32_t align_elems, uint64_t min_count, uint64_t* split_out);
+
+/* ------------------------------------------------------------------------
+ * Communicator (paper: Section "Communicator").
+ * ---------------------------------------------------------------------- */
+typedef struct flex_config {
+    uint64_t chunk_bytes;        /* size of one pinned transit buffer (paper: 4 MB; default 4 MiB) */
+    uint32_t num_slots;          /* transit buffers in the ring; 2 = the paper's double buffering */
+    uint32_t max_host_units;     /* largest host share a call may use; sizes the device scratch
+                                    (default 2500 = 25 %) */
+    uint32_t split_align_elems;  /* alignment of the cut, elements (default 2048) */
+    uint64_t min_split_bytes;    /* messages shorter than this per rank are never split (default 64 KiB) */
+    uint32_t tune_reps;          /* collective calls per MeasurePathTimings in flex_comm_tune (default 5) */
+    uint32_t probe_units;        /* host share used to measure the host path's rate (default 200) */
+    /* launch shapes of the two kernels; 0 = library default */
+    uint32_t reduce_threads;     /* workgroup size of the N-way reduce kernel (64..1024, multiple of 64) */
+    uint32_t reduce_unroll;      /* 16-byte vectors per thread per input per tile: 1, 2 or 4 */
+    uint32_t reduce_waves_per_cu;/* 0 = one workgroup per tile; else a persistent grid sized to this many
+                                    wavefronts per compute unit, striding over tiles */
+    uint32_t copy_threads;
+    uint32_t copy_unroll;        /* 1, 2, 4 or 8 */
+    uint32_t copy_waves_per_cu;
+    uint32_t nontemporal;        /* 1 = mark streaming loads/stores non-temporal (default), 0 = plain */
+    uint32_t reserved;
+    flex_balancer_cfg_t balancer;
+} flex_config_t;
+
+typedef struct flex_stats {
+    uint64_t calls;              /* collective calls of this kind since creation */
+    uint64_t split_calls;        /* of which used both paths */
+    uint64_t samples;            /* per-path timings the Evaluator has read back */
+    uint64_t blocking_reads;     /* times the Evaluator had to wait for an old call because its record
+                                    ring was full (0 in normal operation) */
+    uint64_t last_count;         /* elements per rank of the last call */
+    uint64_t last_split;         /* its cut: device part [0,split), host part [split,count) */
+    uint32_t mode;               /* flex_split_mode */
+    uint32_t static_host_units;
+    double last_time_s[FLEX_MAX_PATHS]; /* latest per-path completion times read back (0 = none) */
+    double mean_time_s[FLEX_MAX_PATHS]; /* mean over all samples */
+    flex_balancer_state_t balancer;     /* state for the size class of the queried message
+                                           (npaths == 0 if that class has none) */
+} flex_stats_t;
+
+typedef struct flex_tune_result {
+    double path_bw[FLEX_MAX_PATHS];         /* measured rates, message bytes per second */
+    uint32_t initial_shares[FLEX_MAX_PATHS];/* InitializeShares' result */
+    uint32_t shares[FLEX_MAX_PATHS];        /* shares after Algorithm 1 */
+    uint32_t active_mask;
+    uint32_t iterations;                    /* Algorithm 1 iterations measured */
+    double path_time_s[FLEX_MAX_PATHS];     /* last measured per-path times */
+} flex_tune_result_t;
+
+/* Fill *cfg (host pointer) with defaults. */
+int flex_config_default(flex_config_t* cfg);
+
+/* Create a communicator on the current HIP device.
+ *   comm                host pointer; receives the object.
+ *   nranks              simulated ranks, 1..FLEX_MAX_RANKS.
+ *   rank                which rank this GPU plays, 0..nranks-1: that rank's
+ *                       buffer is local and never takes the host path.
+ *   max_bytes_per_rank  largest per-rank message any later call will pass.
+ *   cfg                 host pointer or NULL for defaults.
+ * Allocates, once: num_slots pinned buffers of chunk_bytes, a device scratch of
+ * (nranks-1) * ceil(max_bytes_per_rank * max_host_units / share_total) bytes
+ * (rounded up), two side streams at default priority, and an event ring.
+ * Nothing is allocated per call afterwards.
+ * Errors: INVALID_ARG, NOMEM, HIP. */
+int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_per_rank,
+                     const flex_config_t* cfg);
+
+/* Wait for all work this communicator enqueued on its side streams, then free
+ * everything it owns.  NULL is accepted. */
+int flex_comm_destroy(flex_comm_t* comm);
+
+/* AllReduce(sum), local share (paper: Evaluation, "End-to-End Performance" -
+ * ring AllReduce = reduce-scatter with a reduce-sum, then all-gather; the
+ * abstract's "lossless": the result is the same whatever the split).
+ *   rank_bufs  host array of nranks device pointers; rank_bufs[r] holds rank
+ *              r's `count` contiguous elements.  The array itself is only read
+ *              during the call.
+ *   out        device pointer to `count` elements.
+ *   count      elements per rank (0 is allowed: nothing is enqueued).
+ *   dtype      FLEX_F32 or FLEX_BF16.   op: FLEX_SUM.
+ *   hip_stream the caller's hipStream_t (NULL = the default stream).
+ * Result, for every i:  out[i] = round(((b0[i] + b1[i]) + b2[i]) + ... ) with
+ * the additions done in IEEE binary32, round-to-nearest-even, strictly in rank
+ * order starting from rank 0's value, and one final rounding to dtype
+ * (bfloat16: round-to-nearest-even; a NaN result is some quiet NaN).  The bits
+ * of out do not depend on the split, the chunk size, `rank` or the launch
+ * shape.  Elements [0, split) are reduced by the device path on hip_stream;
+ * peers' elements [split, count) travel through the pinned transit buffers into
+ * device scratch on the side streams and are reduced there, in the same rank
+ * order, together with the local rank's elements read in place.
+ * Pointers need no particular alignment (16-byte aligned ones take the fast
+ * path).  out may be the same buffer as rank_bufs[rank]; any other overlap
+ * between out and an input is undefined.
+ * Errors: INVALID_ARG (null comm/rank_bufs/out/any rank pointer with count > 0,
+ * count * size > max_bytes_per_rank), UNSUPPORTED (dtype, op), HIP. */
+int flex_allreduce_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t count,
+                         int dtype, int op, void* hip_stream);
+
+/* AllGather, local share (paper: same section; N-1 ring steps that place every
+ * rank's slice at its rank offset).
+ *   rank_slices  host array of nranks device pointers to slice_count elements.
+ *   out          device pointer to nranks * slice_count elements.
+ * Result: out[r * slice_count + j] = rank_slices[r][j], bit for bit.  The
+ * device path copies the head [0, split) of every slice on hip_stream; the tail
+ * [split, slice_count) of every peer slice goes through the transit buffers
+ * straight to its place in out (the local slice is copied whole by the device
+ * path).  rank_slices[rank] may already be out + rank * slice_count (in-place
+ * convention): it is then not copied.  Errors as for flex_allreduce_local. */
+int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
+                         size_t slice_count, int dtype, void* hip_stream);
+
+/* Choose how later calls of collective `coll` are split.
+ *   FLEX_SPLIT_STATIC    every call uses host_units (0 = device path only).
+ *   FLEX_SPLIT_ADAPTIVE  calls use the share vector of the balancer that
+ *                        belongs to the message's size class (messages are
+ *                        classed by floor(log2(bytes per rank))); the Evaluator
+ *                        feeds per-path times of finished calls back into it
+ *                        (Stage 2).  A size class that was never tuned borrows
+ *                        the shares of the nearest tuned class of the same
+ *                        collective; with none tuned, calls stay device-only.
+ * Errors: INVALID_ARG (coll, mode, host_units > max_host_units). */
+int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units);
+
+/* Stage 1 on the real hardware (paper: Section "Stage 1: Initial
+ * Coarse-Grained Tuning").  Blocking.  Runs collective `coll` on the given
+ * buffers repeatedly: first to measure each path's rate (device path alone;
+ * host path at probe_units), then Algorithm 1 with MeasurePathTimings = median
+ * of tune_reps calls, until the balancer leaves Stage 1.  The resulting
+ * balancer is stored for the message's size class (replacing an older one).
+ * Arguments as for the collective itself; `out` is overwritten with the
+ * collective's (correct) result.  result may be NULL.
+ * Errors: as the collective, plus STATE if timings cannot be read. */
+int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
+                   int dtype, void* hip_stream, flex_tune_result_t* result);
+
+/* Evaluator: read back the timing records of finished calls without blocking
+ * (also done at the start of every collective call). */
+int flex_evaluator_poll(flex_comm_t* comm);
+
+/* Evaluator: wait until every call issued so far has finished and read all
+ * records back. */
+int flex_evaluator_drain(flex_comm_t* comm);
+
+/* Statistics for collective `coll` and for the size class of a message of
+ * `count` elements of `dtype`.  out: host pointer. */
+int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out);
+
+/* Static strings; never NULL. */
+const char* flex_status_string(int status);
+const char* flex_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXLINK_H */

@@ -1,0 +1,286 @@
+"""ctypes binding of libflexlink.so: same names as the C ABI, argument
+marshalling only.  Every step of the collectives runs inside the library.
+
+torch is used for device memory and streams; it is imported first so that the
+library binds to the HIP runtime torch has already loaded.
+"""
+import ctypes
+import os
+
+import torch  # noqa: F401  (must precede loading the library)
+
+from . import build as _build
+
+FLEX_MAX_RANKS = 8
+FLEX_MAX_PATHS = 4
+
+FLEX_OK, FLEX_ERR_INVALID_ARG, FLEX_ERR_UNSUPPORTED, FLEX_ERR_HIP, FLEX_ERR_NOMEM, FLEX_ERR_STATE = range(6)
+FLEX_F32, FLEX_BF16 = 0, 1
+FLEX_SUM = 0
+FLEX_ALLREDUCE, FLEX_ALLGATHER = 0, 1
+FLEX_PATH_DEVICE, FLEX_PATH_HOST = 0, 1
+FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
+FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
+
+u32, u64, i32, f64 = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double
+
+
+class _Struct(ctypes.Structure):
+    def as_dict(self):
+        out = {}
+        for name, _ in self._fields_:
+            v = getattr(self, name)
+            if isinstance(v, _Struct):
+                v = v.as_dict()
+            elif isinstance(v, ctypes.Array):
+                v = list(v)
+            out[name] = v
+        return out
+
+
+class BalancerCfg(_Struct):
+    _fields_ = [("share_total", u32), ("initial_step", u32), ("stability_required", u32),
+                ("max_tune_iters", u32), ("window", u32), ("runtime_step", u32),
+                ("convergence_threshold", f64), ("runtime_threshold", f64)]
+
+
+class BalancerState(_Struct):
+    _fields_ = [("npaths", u32), ("stage", u32), ("tune_iters", u32), ("step", u32),
+                ("stability_count", u32), ("prev_slowest", i32), ("active_mask", u32),
+                ("window_fill", u32), ("adjustments", u64), ("shares", u32 * FLEX_MAX_PATHS)]
+
+
+class Config(_Struct):
+    _fields_ = [("chunk_bytes", u64), ("num_slots", u32), ("max_host_units", u32),
+                ("split_align_elems", u32), ("min_split_bytes", u64), ("tune_reps", u32),
+                ("probe_units", u32), ("reduce_threads", u32), ("reduce_unroll", u32),
+                ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
+                ("copy_waves_per_cu", u32), ("nontemporal", u32), ("reserved", u32),
+                ("balancer", BalancerCfg)]
+
+
+class Stats(_Struct):
+    _fields_ = [("calls", u64), ("split_calls", u64), ("samples", u64), ("blocking_reads", u64),
+                ("last_count", u64), ("last_split", u64), ("mode", u32), ("static_host_units", u32),
+                ("last_time_s", f64 * FLEX_MAX_PATHS), ("mean_time_s", f64 * FLEX_MAX_PATHS),
+                ("balancer", BalancerState)]
+
+
+class TuneResult(_Struct):
+    _fields_ = [("path_bw", f64 * FLEX_MAX_PATHS), ("initial_shares", u32 * FLEX_MAX_PATHS),
+                ("shares", u32 * FLEX_MAX_PATHS), ("active_mask", u32), ("iterations", u32),
+                ("path_time_s", f64 * FLEX_MAX_PATHS)]
+
+
+class FlexError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("flexlink status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built: there is no
+    fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "libflexlink.so is not built (%s missing); run `python -m paper_2510_15882_amd.build` "
+            "or __graft_entry__.build()" % path)
+    L = ctypes.CDLL(path)
+    vp, pvp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+    sz, ci = ctypes.c_size_t, ctypes.c_int
+    P = ctypes.POINTER
+    sigs = {
+        "flex_balancer_cfg_default": [P(BalancerCfg)],
+        "flex_balancer_init": [pvp, ci, P(f64), P(BalancerCfg)],
+        "flex_balancer_init_shares": [pvp, ci, P(u32), P(BalancerCfg)],
+        "flex_balancer_update": [vp, P(f64), P(u32)],
+        "flex_balancer_finish_tuning": [vp],
+        "flex_balancer_get": [vp, P(BalancerState)],
+        "flex_balancer_destroy": [vp],
+        "flex_partition": [u64, u32, u32, u32, u64, P(u64)],
+        "flex_config_default": [P(Config)],
+        "flex_comm_create": [pvp, ci, ci, sz, P(Config)],
+        "flex_comm_destroy": [vp],
+        "flex_allreduce_local": [vp, pvp, vp, sz, ci, ci, vp],
+        "flex_allgather_local": [vp, pvp, vp, sz, ci, vp],
+        "flex_set_split": [vp, ci, ci, u32],
+        "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
+        "flex_evaluator_poll": [vp],
+        "flex_evaluator_drain": [vp],
+        "flex_get_stats": [vp, ci, sz, ci, P(Stats)],
+    }
+    for name, argtypes in sigs.items():
+        fn = getattr(L, name)
+        fn.argtypes = argtypes
+        fn.restype = ci
+    L.flex_status_string.argtypes = [ci]
+    L.flex_status_string.restype = ctypes.c_char_p
+    L.flex_last_error.argtypes = []
+    L.flex_last_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status):
+    if status != FLEX_OK:
+        raise FlexError(status, lib().flex_last_error().decode())
+
+
+def flex_status_string(status):
+    return lib().flex_status_string(status).decode()
+
+
+def flex_last_error():
+    return lib().flex_last_error().decode()
+
+
+# ------------------------------------------------------------------ balancer
+
+def flex_balancer_cfg_default():
+    cfg = BalancerCfg()
+    _check(lib().flex_balancer_cfg_default(ctypes.byref(cfg)))
+    return cfg
+
+
+def _cfg_ref(cfg):
+    return ctypes.byref(cfg) if cfg is not None else None
+
+
+def flex_balancer_init(path_bw, cfg=None):
+    h = ctypes.c_void_p()
+    arr = (f64 * len(path_bw))(*path_bw)
+    _check(lib().flex_balancer_init(ctypes.byref(h), len(path_bw), arr, _cfg_ref(cfg)))
+    return h
+
+
+def flex_balancer_init_shares(shares, cfg=None):
+    h = ctypes.c_void_p()
+    arr = (u32 * len(shares))(*shares)
+    _check(lib().flex_balancer_init_shares(ctypes.byref(h), len(shares), arr, _cfg_ref(cfg)))
+    return h
+
+
+def flex_balancer_update(b, path_time_s):
+    n = len(path_time_s)
+    t = (f64 * n)(*path_time_s)
+    s = (u32 * n)()
+    _check(lib().flex_balancer_update(b, t, s))
+    return list(s)
+
+
+def flex_balancer_finish_tuning(b):
+    _check(lib().flex_balancer_finish_tuning(b))
+
+
+def flex_balancer_get(b):
+    st = BalancerState()
+    _check(lib().flex_balancer_get(b, ctypes.byref(st)))
+    return st
+
+
+def flex_balancer_destroy(b):
+    _check(lib().flex_balancer_destroy(b))
+
+
+def flex_partition(count, host_units, share_total=10000, align_elems=2048, min_count=32768):
+    out = u64()
+    _check(lib().flex_partition(count, host_units, share_total, align_elems, min_count, ctypes.byref(out)))
+    return out.value
+
+
+# -------------------------------------------------------------- communicator
+
+def flex_config_default():
+    cfg = Config()
+    _check(lib().flex_config_default(ctypes.byref(cfg)))
+    return cfg
+
+
+def dtype_code(dtype):
+    if dtype == torch.float32:
+        return FLEX_F32
+    if dtype == torch.bfloat16:
+        return FLEX_BF16
+    raise ValueError("unsupported dtype %r" % (dtype,))
+
+
+def flex_comm_create(nranks, rank, max_bytes_per_rank, cfg=None):
+    h = ctypes.c_void_p()
+    _check(lib().flex_comm_create(ctypes.byref(h), nranks, rank, max_bytes_per_rank, _cfg_ref(cfg)))
+    return h
+
+
+def flex_comm_destroy(comm):
+    _check(lib().flex_comm_destroy(comm))
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(stream)
+
+
+def _pointer_array(tensors):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr() if isinstance(t, torch.Tensor) else int(t)
+    return arr
+
+
+def _check_tensors(tensors, out):
+    for t in list(tensors) + [out]:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous CUDA tensors")
+        if t.dtype != out.dtype:
+            raise ValueError("dtype mismatch")
+
+
+def flex_allreduce_local(comm, rank_bufs, out, count=None, op=FLEX_SUM, stream=None):
+    """rank_bufs: list of device tensors (one per rank); out: device tensor."""
+    _check_tensors(rank_bufs, out)
+    count = rank_bufs[0].numel() if count is None else count
+    _check(lib().flex_allreduce_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
+                                      dtype_code(out.dtype), op, _stream_handle(stream)))
+
+
+def flex_allgather_local(comm, rank_slices, out, slice_count=None, stream=None):
+    _check_tensors(rank_slices, out)
+    slice_count = rank_slices[0].numel() if slice_count is None else slice_count
+    _check(lib().flex_allgather_local(comm, _pointer_array(rank_slices), out.data_ptr(), slice_count,
+                                      dtype_code(out.dtype), _stream_handle(stream)))
+
+
+def flex_set_split(comm, coll, mode, host_units=0):
+    _check(lib().flex_set_split(comm, coll, mode, host_units))
+
+
+def flex_comm_tune(comm, coll, rank_bufs, out, count=None, stream=None):
+    _check_tensors(rank_bufs, out)
+    count = rank_bufs[0].numel() if count is None else count
+    res = TuneResult()
+    _check(lib().flex_comm_tune(comm, coll, _pointer_array(rank_bufs), out.data_ptr(), count,
+                                dtype_code(out.dtype), _stream_handle(stream), ctypes.byref(res)))
+    return res
+
+
+def flex_evaluator_poll(comm):
+    _check(lib().flex_evaluator_poll(comm))
+
+
+def flex_evaluator_drain(comm):
+    _check(lib().flex_evaluator_drain(comm))
+
+
+def flex_get_stats(comm, coll, count, dtype):
+    st = Stats()
+    _check(lib().flex_get_stats(comm, coll, count, dtype_code(dtype), ctypes.byref(st)))
+    return st

@@ -1,0 +1,750 @@
+// Communicator: partitions each collective over the device path and the
+// host-staged path, runs both concurrently (fork/join by events), and feeds the
+// per-path completion times back to the balancer (the paper's Evaluator).
+// Paper: Design; Section "Communicator"; Section "Two-Stage Load Balancing
+// Strategy".
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+#include "flexlink_internal.h"
+
+namespace flex {
+
+static thread_local char g_last_error[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+}  // namespace flex
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return flex::fail(FLEX_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+    } while (0)
+
+#define LAUNCH_TRY(expr)                                                                       \
+    do {                                                                                       \
+        int e_ = (expr);                                                                       \
+        if (e_ != 0)                                                                           \
+            return flex::fail(FLEX_ERR_HIP, "kernel launch failed: %s",                        \
+                              hipGetErrorString((hipError_t)e_));                              \
+    } while (0)
+
+namespace {
+
+constexpr size_t kRingSize = 256;  // timing records that may be in flight
+
+// One split call's events; the Evaluator reads the elapsed times back later.
+struct TimingRecord {
+    hipEvent_t fork = nullptr, dev_done = nullptr, host_done = nullptr;
+    int coll = 0;
+    int size_class = 0;
+    bool adaptive = false;
+    bool has_device_part = false;
+    uint64_t generation = 0;  // balancer generation the call's shares came from
+};
+
+struct SizeClass {
+    flex::Balancer bal;
+    bool tuned = false;       // produced by flex_comm_tune (else borrowed)
+    uint64_t generation = 0;  // bumped whenever the shares change
+};
+
+struct CollState {
+    uint32_t mode = FLEX_SPLIT_STATIC;
+    uint32_t static_units = 0;
+    std::map<int, SizeClass> classes;
+    uint64_t calls = 0, split_calls = 0, samples = 0;
+    uint64_t last_count = 0, last_split = 0;
+    double last_t[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+    double sum_t[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+};
+
+int size_class_of(size_t bytes) {
+    int c = 0;
+    while (bytes > 1) {
+        bytes >>= 1;
+        ++c;
+    }
+    return c;
+}
+
+}  // namespace
+
+struct flex_comm {
+    int device = 0;
+    int nranks = 0, rank = 0;
+    size_t max_bytes = 0;
+    flex_config_t cfg;
+    flex::LaunchShape reduce_shape, copy_shape;
+
+    hipStream_t s_d2h = nullptr, s_h2d = nullptr;
+    std::vector<void*> pinned;
+    std::vector<hipEvent_t> ev_full, ev_empty;
+    uint64_t chunk_seq = 0;  // chunks staged since creation; slot = seq % num_slots
+
+    char* scratch = nullptr;
+    size_t scratch_stride = 0;  // bytes of scratch per peer
+
+    std::vector<TimingRecord> ring;
+    size_t ring_head = 0, ring_count = 0;
+    uint64_t blocking_reads = 0;
+    hipEvent_t t0 = nullptr, t1 = nullptr;  // device-only timing in flex_comm_tune
+
+    CollState coll[2];
+
+    // ---- host-staged path --------------------------------------------------
+    // Enqueue src -> pinned slot -> dst in chunks.  A slot is refilled only
+    // after the H2D copy that drained it (ev_empty), and drained only after
+    // the D2H copy that filled it (ev_full); the D2H of one chunk overlaps the
+    // H2D of the previous one because they sit on different streams and slots.
+    int stage(const char* src, char* dst, size_t bytes) {
+        const size_t nslots = pinned.size();
+        for (size_t off = 0; off < bytes; off += cfg.chunk_bytes) {
+            const size_t n = std::min<size_t>(cfg.chunk_bytes, bytes - off);
+            const size_t slot = chunk_seq % nslots;
+            if (chunk_seq >= nslots) HIP_TRY(hipStreamWaitEvent(s_d2h, ev_empty[slot], 0));
+            HIP_TRY(hipMemcpyAsync(pinned[slot], src + off, n, hipMemcpyDeviceToHost, s_d2h));
+            HIP_TRY(hipEventRecord(ev_full[slot], s_d2h));
+            HIP_TRY(hipStreamWaitEvent(s_h2d, ev_full[slot], 0));
+            HIP_TRY(hipMemcpyAsync(dst + off, pinned[slot], n, hipMemcpyHostToDevice, s_h2d));
+            HIP_TRY(hipEventRecord(ev_empty[slot], s_h2d));
+            ++chunk_seq;
+        }
+        return FLEX_OK;
+    }
+
+    // ---- Evaluator ---------------------------------------------------------
+    SizeClass* find_class(int c, int size_class) {
+        auto& m = coll[c].classes;
+        auto it = m.find(size_class);
+        return it == m.end() ? nullptr : &it->second;
+    }
+
+    // Size class for an adaptive call: its own, else a copy of the nearest
+    // tuned one of the same collective, else none.
+    SizeClass* class_for_call(int c, int size_class) {
+        if (SizeClass* sc = find_class(c, size_class)) return sc;
+        auto& m = coll[c].classes;
+        const SizeClass* best = nullptr;
+        int best_d = 0;
+        for (auto& kv : m) {
+            if (!kv.second.tuned) continue;
+            int d = std::abs(kv.first - size_class);
+            if (!best || d < best_d) {
+                best = &kv.second;
+                best_d = d;
+            }
+        }
+        if (!best) return nullptr;
+        SizeClass fresh;
+        fresh.bal = best->bal;
+        fresh.bal.finish_tuning();
+        fresh.bal.window.clear();
+        fresh.tuned = false;
+        return &(m[size_class] = fresh);
+    }
+
+    int consume(TimingRecord& rec) {
+        float ms_dev = 0.f, ms_host = 0.f;
+        if (rec.has_device_part) HIP_TRY(hipEventElapsedTime(&ms_dev, rec.fork, rec.dev_done));
+        HIP_TRY(hipEventElapsedTime(&ms_host, rec.fork, rec.host_done));
+        CollState& cs = coll[rec.coll];
+        double T[FLEX_MAX_PATHS] = {ms_dev * 1e-3, ms_host * 1e-3, 0, 0};
+        ++cs.samples;
+        for (int p = 0; p < 2; ++p) {
+            cs.last_t[p] = T[p];
+            cs.sum_t[p] += T[p];
+        }
+        if (rec.adaptive && cs.mode == FLEX_SPLIT_ADAPTIVE) {
+            SizeClass* sc = find_class(rec.coll, rec.size_class);
+            // a call issued before the last share change says nothing about the new shares
+            if (sc && sc->generation == rec.generation && sc->bal.stage == FLEX_STAGE_RUNTIME) {
+                uint32_t before = sc->bal.shares[FLEX_PATH_HOST];
+                if (sc->bal.update(T) && sc->bal.shares[FLEX_PATH_HOST] != before) ++sc->generation;
+            }
+        }
+        return FLEX_OK;
+    }
+
+    int poll(bool block) {
+        while (ring_count > 0) {
+            TimingRecord& rec = ring[ring_head];
+            if (block) {
+                HIP_TRY(hipEventSynchronize(rec.host_done));
+                HIP_TRY(hipEventSynchronize(rec.dev_done));
+            } else {
+                hipError_t q = hipEventQuery(rec.host_done);
+                if (q == hipErrorNotReady) break;
+                if (q != hipSuccess)
+                    return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
+                q = hipEventQuery(rec.dev_done);
+                if (q == hipErrorNotReady) break;
+                if (q != hipSuccess)
+                    return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
+            }
+            int st = consume(rec);
+            ring_head = (ring_head + 1) % kRingSize;
+            --ring_count;
+            if (st) return st;
+        }
+        return FLEX_OK;
+    }
+
+    int acquire_record(TimingRecord** out) {
+        if (ring_count == kRingSize) {
+            // every record is in flight: wait for the oldest one
+            ++blocking_reads;
+            TimingRecord& rec = ring[ring_head];
+            HIP_TRY(hipEventSynchronize(rec.host_done));
+            HIP_TRY(hipEventSynchronize(rec.dev_done));
+            int st = consume(rec);
+            ring_head = (ring_head + 1) % kRingSize;
+            --ring_count;
+            if (st) return st;
+        }
+        *out = &ring[(ring_head + ring_count) % kRingSize];
+        ++ring_count;
+        return FLEX_OK;
+    }
+
+    // Host share, in units, that a call of `bytes` per rank uses now.
+    uint32_t units_for_call(int c, size_t bytes, bool* adaptive, SizeClass** sc_out) {
+        CollState& cs = coll[c];
+        *adaptive = false;
+        *sc_out = nullptr;
+        if (nranks < 2) return 0;
+        if (cs.mode == FLEX_SPLIT_STATIC) return cs.static_units;
+        SizeClass* sc = class_for_call(c, size_class_of(bytes));
+        if (!sc || sc->bal.npaths < 2) return 0;
+        *adaptive = true;
+        *sc_out = sc;
+        return std::min(sc->bal.shares[FLEX_PATH_HOST], cfg.max_host_units);
+    }
+
+    int check_device() const {
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != device)
+            return flex::fail(FLEX_ERR_STATE, "communicator belongs to device %d, current device is %d",
+                              device, cur);
+        return FLEX_OK;
+    }
+
+    int allreduce(const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream);
+    int allgather(const void* const* slices, void* out, size_t count, int dtype, hipStream_t stream);
+    int collective(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream) {
+        return c == FLEX_ALLREDUCE ? allreduce(bufs, out, count, dtype, stream)
+                                   : allgather(bufs, out, count, dtype, stream);
+    }
+    int validate(const char* who, const void* const* bufs, const void* out, size_t count, int dtype);
+    int measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
+                      hipStream_t stream, uint32_t units, double* T);
+};
+
+int flex_comm::validate(const char* who, const void* const* bufs, const void* out, size_t count,
+                        int dtype) {
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
+    if (!bufs) return flex::fail(FLEX_ERR_INVALID_ARG, "%s: rank pointer array is NULL", who);
+    if (count > max_bytes / es)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "%s: %zu elements exceed max_bytes_per_rank %zu", who,
+                          count, max_bytes);
+    if (count == 0) return FLEX_OK;
+    if (!out) return flex::fail(FLEX_ERR_INVALID_ARG, "%s: out is NULL", who);
+    if ((uintptr_t)out % es)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "%s: out is not aligned to the element size", who);
+    for (int r = 0; r < nranks; ++r) {
+        if (!bufs[r]) return flex::fail(FLEX_ERR_INVALID_ARG, "%s: rank %d pointer is NULL", who, r);
+        if ((uintptr_t)bufs[r] % es)
+            return flex::fail(FLEX_ERR_INVALID_ARG, "%s: rank %d pointer is not aligned to the element size",
+                              who, r);
+    }
+    return check_device();
+}
+
+int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int dtype,
+                         hipStream_t stream) {
+    int st = validate("flex_allreduce_local", bufs, out, count, dtype);
+    if (st) return st;
+    CollState& cs = coll[FLEX_ALLREDUCE];
+    ++cs.calls;
+    if (count == 0) return FLEX_OK;
+    st = poll(false);
+    if (st) return st;
+
+    const size_t es = flex::dtype_size(dtype);
+    bool adaptive;
+    SizeClass* sc;
+    const uint32_t units = units_for_call(FLEX_ALLREDUCE, count * es, &adaptive, &sc);
+    const uint64_t split = flex::partition(count, units, cfg.balancer.share_total, cfg.split_align_elems,
+                                           cfg.min_split_bytes / es);
+    const size_t host_count = count - split;
+    cs.last_count = count;
+    cs.last_split = split;
+
+    if (host_count == 0) {
+        LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, count, dtype, reduce_shape, stream));
+        return FLEX_OK;
+    }
+    if (host_count * es > scratch_stride)
+        return flex::fail(FLEX_ERR_INVALID_ARG,
+                          "flex_allreduce_local: host part of %zu bytes exceeds the scratch sized by "
+                          "max_host_units (%zu bytes per peer)",
+                          host_count * es, scratch_stride);
+
+    ++cs.split_calls;
+    TimingRecord* rec;
+    st = acquire_record(&rec);
+    if (st) return st;
+    rec->coll = FLEX_ALLREDUCE;
+    rec->size_class = size_class_of(count * es);
+    rec->adaptive = adaptive;
+    rec->generation = sc ? sc->generation : 0;
+    rec->has_device_part = split > 0;
+
+    // fork
+    HIP_TRY(hipEventRecord(rec->fork, stream));
+    HIP_TRY(hipStreamWaitEvent(s_d2h, rec->fork, 0));
+
+    // device path: head of the message, straight from HBM
+    if (split > 0) LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, split, dtype, reduce_shape, stream));
+    HIP_TRY(hipEventRecord(rec->dev_done, stream));
+
+    // host path: every peer's tail goes device -> pinned -> device scratch ...
+    const void* tail_in[FLEX_MAX_RANKS];
+    int peer = 0;
+    for (int r = 0; r < nranks; ++r) {
+        const char* src = (const char*)bufs[r] + split * es;
+        if (r == rank) {
+            tail_in[r] = src;  // the local contribution never leaves the device
+            continue;
+        }
+        char* dst = scratch + (size_t)peer * scratch_stride;
+        st = stage(src, dst, host_count * es);
+        if (st) return st;
+        tail_in[r] = dst;
+        ++peer;
+    }
+    // ... and is reduced there in the same rank order
+    LAUNCH_TRY(flex::launch_reduce_n(tail_in, nranks, (char*)out + split * es, host_count, dtype,
+                                     reduce_shape, s_h2d));
+    HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
+
+    // join
+    HIP_TRY(hipStreamWaitEvent(stream, rec->host_done, 0));
+    return FLEX_OK;
+}
+
+int flex_comm::allgather(const void* const* slices, void* out, size_t count, int dtype,
+                         hipStream_t stream) {
+    int st = validate("flex_allgather_local", slices, out, count, dtype);
+    if (st) return st;
+    CollState& cs = coll[FLEX_ALLGATHER];
+    ++cs.calls;
+    if (count == 0) return FLEX_OK;
+    st = poll(false);
+    if (st) return st;
+
+    const size_t es = flex::dtype_size(dtype);
+    const size_t slice_bytes = count * es;
+    bool adaptive;
+    SizeClass* sc;
+    const uint32_t units = units_for_call(FLEX_ALLGATHER, slice_bytes, &adaptive, &sc);
+    const uint64_t split = flex::partition(count, units, cfg.balancer.share_total, cfg.split_align_elems,
+                                           cfg.min_split_bytes / es);
+    const size_t host_bytes = (count - split) * es;
+    cs.last_count = count;
+    cs.last_split = split;
+
+    const void* src[FLEX_MAX_RANKS];
+    void* dst[FLEX_MAX_RANKS];
+    uint64_t bytes[FLEX_MAX_RANKS];
+    for (int r = 0; r < nranks; ++r) {
+        src[r] = slices[r];
+        dst[r] = (char*)out + (size_t)r * slice_bytes;
+        bytes[r] = (r == rank) ? slice_bytes : split * es;  // local slice: whole, on the device path
+    }
+
+    if (host_bytes == 0) {
+        LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
+        return FLEX_OK;
+    }
+
+    ++cs.split_calls;
+    TimingRecord* rec;
+    st = acquire_record(&rec);
+    if (st) return st;
+    rec->coll = FLEX_ALLGATHER;
+    rec->size_class = size_class_of(slice_bytes);
+    rec->adaptive = adaptive;
+    rec->generation = sc ? sc->generation : 0;
+    rec->has_device_part = true;
+
+    HIP_TRY(hipEventRecord(rec->fork, stream));
+    HIP_TRY(hipStreamWaitEvent(s_d2h, rec->fork, 0));
+
+    LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
+    HIP_TRY(hipEventRecord(rec->dev_done, stream));
+
+    for (int r = 0; r < nranks; ++r) {
+        if (r == rank) continue;
+        st = stage((const char*)slices[r] + split * es, (char*)dst[r] + split * es, host_bytes);
+        if (st) return st;
+    }
+    HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
+    HIP_TRY(hipStreamWaitEvent(stream, rec->host_done, 0));
+    return FLEX_OK;
+}
+
+// MeasurePathTimings of Algorithm 1: median per-path time of cfg.tune_reps
+// calls at a fixed host share.  T[path] in seconds.
+int flex_comm::measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
+                             hipStream_t stream, uint32_t units, double* T) {
+    CollState& cs = coll[c];
+    cs.mode = FLEX_SPLIT_STATIC;
+    cs.static_units = units;
+    std::vector<double> td, th;
+    for (uint32_t k = 0; k < cfg.tune_reps + 1; ++k) {
+        const uint64_t before = cs.samples;
+        int st = collective(c, bufs, out, count, dtype, stream);
+        if (st) return st;
+        st = poll(true);
+        if (st) return st;
+        if (cs.samples == before)
+            return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: a split call produced no timing sample");
+        if (k == 0) continue;  // first call warms the path up
+        td.push_back(cs.last_t[FLEX_PATH_DEVICE]);
+        th.push_back(cs.last_t[FLEX_PATH_HOST]);
+    }
+    std::sort(td.begin(), td.end());
+    std::sort(th.begin(), th.end());
+    const size_t n = td.size();
+    T[FLEX_PATH_DEVICE] = (n & 1) ? td[n / 2] : (td[n / 2 - 1] + td[n / 2]) / 2.0;
+    T[FLEX_PATH_HOST] = (n & 1) ? th[n / 2] : (th[n / 2 - 1] + th[n / 2]) / 2.0;
+    return FLEX_OK;
+}
+
+extern "C" {
+
+int flex_config_default(flex_config_t* cfg) {
+    if (!cfg) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_config_default: cfg is NULL");
+    memset(cfg, 0, sizeof *cfg);
+    cfg->chunk_bytes = 4u << 20;
+    cfg->num_slots = 2;
+    cfg->max_host_units = 2500;
+    cfg->split_align_elems = 2048;
+    cfg->min_split_bytes = 64u << 10;
+    cfg->tune_reps = 5;
+    cfg->probe_units = 200;
+    cfg->reduce_threads = 256;
+    cfg->reduce_unroll = 2;
+    cfg->reduce_waves_per_cu = 0;
+    cfg->copy_threads = 256;
+    cfg->copy_unroll = 4;
+    cfg->copy_waves_per_cu = 0;
+    cfg->nontemporal = 1;
+    flex::balancer_cfg_default(&cfg->balancer);
+    return FLEX_OK;
+}
+
+static bool threads_ok(uint32_t t) { return t >= 64 && t <= 1024 && t % 64 == 0; }
+
+int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_per_rank,
+                     const flex_config_t* cfg) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_create: comm is NULL");
+    *comm = nullptr;
+    if (nranks < 1 || nranks > FLEX_MAX_RANKS || rank < 0 || rank >= nranks)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_create: nranks %d / rank %d out of range", nranks,
+                          rank);
+    flex_config_t c;
+    flex_config_default(&c);
+    if (cfg) {
+        flex_config_t d = c;
+        c = *cfg;
+        // zero means "library default" for the launch shapes
+        if (!c.reduce_threads) c.reduce_threads = d.reduce_threads;
+        if (!c.reduce_unroll) c.reduce_unroll = d.reduce_unroll;
+        if (!c.copy_threads) c.copy_threads = d.copy_threads;
+        if (!c.copy_unroll) c.copy_unroll = d.copy_unroll;
+    }
+    const flex_balancer_cfg_t& b = c.balancer;
+    if (c.chunk_bytes < 4096 || c.chunk_bytes % 16 || c.num_slots < 1 || c.num_slots > 64 ||
+        b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
+        c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
+        !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_create: configuration out of range");
+
+    flex_comm* m = new (std::nothrow) flex_comm;
+    if (!m) return flex::fail(FLEX_ERR_NOMEM, "flex_comm_create: out of host memory");
+    m->nranks = nranks;
+    m->rank = rank;
+    m->max_bytes = max_bytes_per_rank;
+    m->cfg = c;
+
+#define CREATE_TRY(expr)                                                                      \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            int code_ = (e_ == hipErrorOutOfMemory) ? FLEX_ERR_NOMEM : FLEX_ERR_HIP;          \
+            flex::fail(code_, "flex_comm_create: %s failed: %s", #expr, hipGetErrorString(e_)); \
+            flex_comm_destroy(m);                                                             \
+            return code_;                                                                     \
+        }                                                                                     \
+    } while (0)
+
+    CREATE_TRY(hipGetDevice(&m->device));
+    int cus = 0;
+    CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
+    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.nontemporal, (uint32_t)cus};
+    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.nontemporal, (uint32_t)cus};
+
+    // Side streams at the default priority.
+    CREATE_TRY(hipStreamCreateWithFlags(&m->s_d2h, hipStreamNonBlocking));
+    CREATE_TRY(hipStreamCreateWithFlags(&m->s_h2d, hipStreamNonBlocking));
+    CREATE_TRY(hipEventCreate(&m->t0));
+    CREATE_TRY(hipEventCreate(&m->t1));
+
+    if (nranks > 1) {
+        for (uint32_t s = 0; s < c.num_slots; ++s) {
+            void* p = nullptr;
+            CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes, hipHostMallocDefault));
+            m->pinned.push_back(p);
+            hipEvent_t e = nullptr;
+            CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            m->ev_full.push_back(e);
+            e = nullptr;
+            CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            m->ev_empty.push_back(e);
+        }
+        // scratch: per peer, the largest host part a call may have (rounded up
+        // by one alignment quantum of the widest element and to 256 bytes)
+        unsigned __int128 part = (unsigned __int128)max_bytes_per_rank * c.max_host_units;
+        size_t per_peer = (size_t)((part + b.share_total - 1) / b.share_total);
+        per_peer += (size_t)c.split_align_elems * 4 * 2;
+        per_peer = std::min(per_peer, max_bytes_per_rank);
+        per_peer = (per_peer + 255) / 256 * 256;
+        m->scratch_stride = per_peer;
+        if (c.max_host_units > 0 && max_bytes_per_rank > 0)
+            CREATE_TRY(hipMalloc((void**)&m->scratch, per_peer * (size_t)(nranks - 1)));
+        m->ring.resize(kRingSize);
+        for (auto& rec : m->ring) {
+            CREATE_TRY(hipEventCreate(&rec.fork));
+            CREATE_TRY(hipEventCreate(&rec.dev_done));
+            CREATE_TRY(hipEventCreate(&rec.host_done));
+        }
+    }
+#undef CREATE_TRY
+    *comm = m;
+    return FLEX_OK;
+}
+
+int flex_comm_destroy(flex_comm_t* m) {
+    if (!m) return FLEX_OK;
+    if (m->s_d2h) (void)hipStreamSynchronize(m->s_d2h);
+    if (m->s_h2d) (void)hipStreamSynchronize(m->s_h2d);
+    for (auto& rec : m->ring) {
+        if (rec.fork) (void)hipEventDestroy(rec.fork);
+        if (rec.dev_done) (void)hipEventDestroy(rec.dev_done);
+        if (rec.host_done) (void)hipEventDestroy(rec.host_done);
+    }
+    for (auto e : m->ev_full) (void)hipEventDestroy(e);
+    for (auto e : m->ev_empty) (void)hipEventDestroy(e);
+    for (auto p : m->pinned) (void)hipHostFree(p);
+    if (m->scratch) (void)hipFree(m->scratch);
+    if (m->t0) (void)hipEventDestroy(m->t0);
+    if (m->t1) (void)hipEventDestroy(m->t1);
+    if (m->s_d2h) (void)hipStreamDestroy(m->s_d2h);
+    if (m->s_h2d) (void)hipStreamDestroy(m->s_h2d);
+    delete m;
+    return FLEX_OK;
+}
+
+int flex_allreduce_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t count,
+                         int dtype, int op, void* hip_stream) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_allreduce_local: comm is NULL");
+    if (op != FLEX_SUM) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_allreduce_local: unknown op %d", op);
+    return comm->allreduce(rank_bufs, out, count, dtype, (hipStream_t)hip_stream);
+}
+
+int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
+                         size_t slice_count, int dtype, void* hip_stream) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_allgather_local: comm is NULL");
+    return comm->allgather(rank_slices, out, slice_count, dtype, (hipStream_t)hip_stream);
+}
+
+int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: comm is NULL");
+    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown collective %d", coll);
+    if (mode != FLEX_SPLIT_STATIC && mode != FLEX_SPLIT_ADAPTIVE)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown mode %d", mode);
+    if (mode == FLEX_SPLIT_STATIC && host_units > comm->cfg.max_host_units)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: host share %u exceeds max_host_units %u",
+                          host_units, comm->cfg.max_host_units);
+    comm->coll[coll].mode = (uint32_t)mode;
+    if (mode == FLEX_SPLIT_STATIC) comm->coll[coll].static_units = host_units;
+    return FLEX_OK;
+}
+
+int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
+                   int dtype, void* hip_stream, flex_tune_result_t* result) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: comm is NULL");
+    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: unknown collective %d", coll);
+    int st = comm->validate("flex_comm_tune", rank_bufs, out, count, dtype);
+    if (st) return st;
+    if (count == 0) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: empty message");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    CollState& cs = comm->coll[coll];
+    const uint32_t saved_mode = cs.mode, saved_units = cs.static_units;
+    const size_t es = flex::dtype_size(dtype);
+    const double msg_bytes = (double)count * es;
+    const flex_balancer_cfg_t& bc = comm->cfg.balancer;
+    flex_tune_result_t res;
+    memset(&res, 0, sizeof res);
+
+    struct Restore {
+        CollState& cs;
+        uint32_t mode, units;
+        ~Restore() {
+            cs.mode = mode;
+            cs.static_units = units;
+        }
+    } restore{cs, saved_mode, saved_units};
+
+    st = comm->poll(true);
+    if (st) return st;
+
+    // Rate of the device path carrying the whole message alone.
+    cs.mode = FLEX_SPLIT_STATIC;
+    cs.static_units = 0;
+    std::vector<double> td;
+    for (uint32_t k = 0; k < comm->cfg.tune_reps + 1; ++k) {
+        HIP_TRY(hipEventRecord(comm->t0, stream));
+        st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
+        if (st) return st;
+        HIP_TRY(hipEventRecord(comm->t1, stream));
+        HIP_TRY(hipEventSynchronize(comm->t1));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, comm->t0, comm->t1));
+        if (k > 0) td.push_back(ms * 1e-3);
+    }
+    std::sort(td.begin(), td.end());
+    const double t_dev_alone = td[td.size() / 2];
+    res.path_bw[FLEX_PATH_DEVICE] = t_dev_alone > 0 ? msg_bytes / t_dev_alone : 0.0;
+
+    // Rate of the host path, measured on a probe share of the message.
+    double T[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+    uint32_t probe = std::min(comm->cfg.probe_units, comm->cfg.max_host_units);
+    uint64_t split = count;
+    if (comm->nranks > 1 && probe > 0)
+        split = flex::partition(count, probe, bc.share_total, comm->cfg.split_align_elems,
+                                comm->cfg.min_split_bytes / es);
+    if (split < count && (count - split) * es <= comm->scratch_stride) {
+        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, probe, T);
+        if (st) return st;
+        res.path_bw[FLEX_PATH_HOST] = T[FLEX_PATH_HOST] > 0 ? (double)(count - split) * es / T[FLEX_PATH_HOST] : 0.0;
+    }
+
+    SizeClass sc;
+    sc.tuned = true;
+    if (!(res.path_bw[FLEX_PATH_DEVICE] > 0) ||
+        !sc.bal.init_from_bandwidth(2, res.path_bw, bc))
+        return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: could not measure the device path");
+    for (int p = 0; p < 2; ++p) res.initial_shares[p] = sc.bal.shares[p];
+
+    // Algorithm 1 with real measurements.
+    while (sc.bal.stage == FLEX_STAGE_TUNING) {
+        uint32_t units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, T);
+        if (st) return st;
+        if (!sc.bal.update(T))
+            return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: unusable path timings (%g s, %g s)", T[0], T[1]);
+    }
+    // leave `out` holding a result computed after the last share change
+    cs.static_units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+    st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
+    if (st) return st;
+    HIP_TRY(hipStreamSynchronize(stream));
+    st = comm->poll(true);
+    if (st) return st;
+
+    for (int p = 0; p < 2; ++p) {
+        res.shares[p] = sc.bal.shares[p];
+        res.path_time_s[p] = T[p];
+    }
+    res.active_mask = sc.bal.active_mask;
+    res.iterations = sc.bal.tune_iters;
+    auto& slot = cs.classes[size_class_of(count * es)];
+    const uint64_t gen = slot.generation + 1;
+    slot = sc;
+    slot.generation = gen;
+    if (result) *result = res;
+    return FLEX_OK;
+}
+
+int flex_evaluator_poll(flex_comm_t* comm) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_evaluator_poll: comm is NULL");
+    return comm->poll(false);
+}
+
+int flex_evaluator_drain(flex_comm_t* comm) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_evaluator_drain: comm is NULL");
+    return comm->poll(true);
+}
+
+int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out) {
+    if (!comm || !out) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: NULL argument");
+    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: unknown collective %d", coll);
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_get_stats: unknown dtype %d", dtype);
+    memset(out, 0, sizeof *out);
+    const CollState& cs = comm->coll[coll];
+    out->calls = cs.calls;
+    out->split_calls = cs.split_calls;
+    out->samples = cs.samples;
+    out->blocking_reads = comm->blocking_reads;
+    out->last_count = cs.last_count;
+    out->last_split = cs.last_split;
+    out->mode = cs.mode;
+    out->static_host_units = cs.static_units;
+    for (int p = 0; p < FLEX_MAX_PATHS; ++p) {
+        out->last_time_s[p] = cs.last_t[p];
+        out->mean_time_s[p] = cs.samples ? cs.sum_t[p] / (double)cs.samples : 0.0;
+    }
+    if (SizeClass* sc = comm->find_class(coll, size_class_of(count * es))) sc->bal.get(&out->balancer);
+    return FLEX_OK;
+}
+
+const char* flex_status_string(int status) {
+    switch (status) {
+        case FLEX_OK: return "ok";
+        case FLEX_ERR_INVALID_ARG: return "invalid argument";
+        case FLEX_ERR_UNSUPPORTED: return "unsupported dtype, op or collective";
+        case FLEX_ERR_HIP: return "HIP runtime error";
+        case FLEX_ERR_NOMEM: return "out of memory";
+        case FLEX_ERR_STATE: return "invalid state";
+        default: return "unknown status";
+    }
+}
+
+const char* flex_last_error(void) { return flex::g_last_error; }
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of libflexlink.
+#ifndef FLEXLINK_INTERNAL_H
+#define FLEXLINK_INTERNAL_H
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "flexlink.h"
+
+namespace flex {
+
+// Records a message for flex_last_error() and returns `status`.
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+void balancer_cfg_default(flex_balancer_cfg_t* c);
+
+// Cut between the device part [0, split) and the host part [split, count).
+inline uint64_t partition(uint64_t count, uint32_t host_units, uint32_t share_total, uint32_t align,
+                          uint64_t min_count) {
+    if (host_units == 0 || count < min_count || count < align) return count;
+    if (host_units >= share_total) return 0;
+    uint64_t owed = (uint64_t)(((unsigned __int128)count * host_units) / share_total);
+    uint64_t split = ((count - owed) / align) * align;
+    if (split == count) split = count - align;
+    return split;
+}
+
+// Algorithm 1 as a state machine plus the Stage-2 window logic.
+struct Balancer {
+    struct Sample {
+        double t[FLEX_MAX_PATHS];
+    };
+    flex_balancer_cfg_t cfg;
+    int npaths = 0;
+    uint32_t shares[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+    uint32_t active_mask = 0;
+    uint32_t stage = FLEX_STAGE_TUNING;
+    uint32_t tune_iters = 0;
+    uint32_t step = 0;
+    uint32_t stability_count = 0;
+    int32_t prev_slowest = -1;
+    uint64_t adjustments = 0;
+    std::vector<Sample> window;
+
+    bool init_from_bandwidth(int np, const double* bw, const flex_balancer_cfg_t& c);
+    bool init_from_shares(int np, const uint32_t* s, const flex_balancer_cfg_t& c);
+    bool update(const double* T);  // false: bad times, state unchanged
+    void finish_tuning();
+    void get(flex_balancer_state_t* o) const;
+
+   private:
+    void end_tuning_if_done(bool stable);
+    void slowest_fastest(const double* T, int* slow, int* fast) const;
+    void move_share(int slow, int fast, uint32_t amount);
+    bool times_ok(const double* T) const;
+};
+
+// ---- device path launchers (defined in reduce_n.hip / gather_copy.hip) ----
+
+struct LaunchShape {
+    uint32_t threads;       // workgroup size
+    uint32_t unroll;        // 16-byte vectors per thread per input per tile
+    uint32_t waves_per_cu;  // 0 = one workgroup per tile
+    uint32_t nontemporal;
+    uint32_t num_cus;       // compute units of the device
+};
+
+// Enqueue out[i] = sum over r (rank order) of in[r][i], i in [0, count), on
+// `stream`.  Pointers are device pointers with no alignment requirement.
+// Returns a hipError_t value as int (0 = success).
+int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int dtype,
+                    const LaunchShape& shape, void* stream);
+
+// Enqueue, for r in [0, n): copy bytes[r] bytes from src[r] to dst[r] on
+// `stream`; pairs with src[r] == dst[r] or bytes[r] == 0 are skipped.
+int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t* bytes, int n,
+                       const LaunchShape& shape, void* stream);
+
+inline size_t dtype_size(int dtype) { return dtype == FLEX_F32 ? 4 : dtype == FLEX_BF16 ? 2 : 0; }
+
+}  // namespace flex
+
+#endif

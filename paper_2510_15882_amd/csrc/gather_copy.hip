@@ -1,0 +1,160 @@
+// Chunked gather/copy: the data movement a rank performs in the all-gather half
+// of the paper's ring collectives (Evaluation, "End-to-End Performance": N-1
+// steps, each placing one rank's slice at its rank offset), done for all N
+// slices in a single launch.
+//
+// Pure HBM streaming for gfx950: blockIdx.y selects the slice, lanes move
+// 16-byte vectors so that a wavefront covers 1 KiB contiguously, UNROLL loads
+// are in flight per lane before the first store.  Bytes are never interpreted.
+#include <hip/hip_runtime.h>
+
+#include "flexlink_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct CopyArgs {
+    const void* src[FLEX_MAX_RANKS];
+    void* dst[FLEX_MAX_RANKS];
+    uint64_t bytes[FLEX_MAX_RANKS];
+};
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// Copy in granules of sizeof(G) bytes when source and destination only agree
+// modulo sizeof(G): byte-wise head until both are G-aligned, G-wise body,
+// byte-wise tail.  All workgroups of the slice stride over it together.
+template <typename G>
+__device__ void copy_granules(const char* s, char* d, uint64_t bytes) {
+    const uint64_t gtid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t gsize = (uint64_t)gridDim.x * blockDim.x;
+    uint64_t head = (sizeof(G) - ((uintptr_t)s & (sizeof(G) - 1))) & (sizeof(G) - 1);
+    if (head > bytes) head = bytes;
+    const uint64_t nbody = (bytes - head) / sizeof(G);
+    const G* sb = (const G*)(s + head);
+    G* db = (G*)(d + head);
+    for (uint64_t k = gtid; k < nbody; k += gsize) db[k] = sb[k];
+    const uint64_t body_end = head + nbody * sizeof(G);
+    const uint64_t nloose = head + (bytes - body_end);
+    for (uint64_t k = gtid; k < nloose; k += gsize) {
+        const uint64_t i = k < head ? k : body_end + (k - head);
+        d[i] = s[i];
+    }
+}
+
+template <int UNROLL, bool NT>
+__global__ void gather_copy_kernel(CopyArgs a) {
+    const int r = blockIdx.y;
+    const char* s = (const char*)a.src[r];
+    char* d = (char*)a.dst[r];
+    const uint64_t bytes = a.bytes[r];
+    if (s == d || bytes == 0) return;  // slice already in place
+
+    const uintptr_t diff = (uintptr_t)s ^ (uintptr_t)d;
+    if (diff & 15) {
+        // source and destination disagree within a 16-byte line
+        if ((diff & 3) == 0)
+            copy_granules<uint32_t>(s, d, bytes);
+        else if ((diff & 1) == 0)
+            copy_granules<uint16_t>(s, d, bytes);
+        else
+            copy_granules<uint8_t>(s, d, bytes);
+        return;
+    }
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nthreads = blockDim.x;
+    uint64_t head = (16 - ((uintptr_t)s & 15)) & 15;
+    if (head > bytes) head = bytes;
+    const uint64_t nvec = (bytes - head) / 16;
+    const u32x4* in = (const u32x4*)(s + head);
+    u32x4* out = (u32x4*)(d + head);
+    const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
+    const uint64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+
+    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const uint64_t first = tile * tile_vecs;
+        if (first + tile_vecs <= nvec) {
+            u32x4 v[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) v[u] = load16<NT>(in + first + (uint64_t)u * nthreads + tid);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) store16<NT>(out + first + (uint64_t)u * nthreads + tid, v[u]);
+        } else {
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint64_t idx = first + (uint64_t)u * nthreads + tid;
+                if (idx < nvec) store16<NT>(out + idx, load16<NT>(in + idx));
+            }
+        }
+    }
+
+    // bytes outside the aligned body (at most 15 on each side)
+    const uint64_t body_end = head + nvec * 16;
+    const uint64_t nloose = head + (bytes - body_end);
+    if (blockIdx.x == 0) {
+        for (uint64_t k = tid; k < nloose; k += nthreads) {
+            const uint64_t i = k < head ? k : body_end + (k - head);
+            d[i] = s[i];
+        }
+    }
+}
+
+template <int UNROLL, bool NT>
+int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, hipStream_t stream) {
+    hipLaunchKernelGGL((gather_copy_kernel<UNROLL, NT>), grid, dim3(threads), 0, stream, a);
+    return (int)hipGetLastError();
+}
+
+}  // namespace
+
+namespace flex {
+
+int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t* bytes, int n,
+                       const LaunchShape& shape, void* stream) {
+    CopyArgs a;
+    uint64_t longest = 0;
+    for (int r = 0; r < FLEX_MAX_RANKS; ++r) {
+        a.src[r] = r < n ? src[r] : nullptr;
+        a.dst[r] = r < n ? dst[r] : nullptr;
+        a.bytes[r] = r < n ? bytes[r] : 0;
+        if (r < n && src[r] != dst[r] && bytes[r] > longest) longest = bytes[r];
+    }
+    if (longest == 0) return 0;
+
+    const uint32_t threads = shape.threads;
+    const uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : shape.unroll == 8 ? 8 : 4;
+    const uint64_t tile_bytes = (uint64_t)threads * unroll * 16;
+    uint64_t gx = (longest + tile_bytes - 1) / tile_bytes;
+    if (shape.waves_per_cu) {
+        uint64_t resident = (uint64_t)shape.num_cus * shape.waves_per_cu * 64 / threads;
+        uint64_t per_slice = (resident + n - 1) / n;
+        if (per_slice == 0) per_slice = 1;
+        if (gx > per_slice) gx = per_slice;
+    }
+    if (gx == 0) gx = 1;
+    if (gx > 0x7fffffffull) gx = 0x7fffffffull;
+    dim3 grid((uint32_t)gx, (uint32_t)n, 1);
+    hipStream_t s = (hipStream_t)stream;
+    const bool nt = shape.nontemporal != 0;
+    switch (unroll) {
+        case 1: return nt ? launch_one<1, true>(a, grid, threads, s) : launch_one<1, false>(a, grid, threads, s);
+        case 2: return nt ? launch_one<2, true>(a, grid, threads, s) : launch_one<2, false>(a, grid, threads, s);
+        case 8: return nt ? launch_one<8, true>(a, grid, threads, s) : launch_one<8, false>(a, grid, threads, s);
+        default: return nt ? launch_one<4, true>(a, grid, threads, s) : launch_one<4, false>(a, grid, threads, s);
+    }
+}
+
+}  // namespace flex

@@ -1,0 +1,238 @@
+// N-way rank-ordered reduction: the arithmetic a rank performs in the
+// reduce-scatter half of the paper's ring AllReduce ("reduce sum computation",
+// Limitations and Future Work), fused over all N contributions.
+//
+// Pure HBM streaming for gfx950: every lane issues one 16-byte load per input
+// per unrolled step (a wavefront covers 1 KiB of each input contiguously), all
+// N * UNROLL loads of a tile are in flight before the first add, and the result
+// leaves through one 16-byte store.  No LDS and no MFMA: 7 adds per 18 bytes.
+//
+// The sum is taken strictly in rank order in binary32, starting from rank 0's
+// value, and rounded once to the element type; nothing here may be compiled
+// with fast-math, reassociation or denormal flushing.
+#include <hip/hip_runtime.h>
+
+#include "flexlink_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct ReduceArgs {
+    const void* in[FLEX_MAX_RANKS];
+    void* out;
+    uint64_t head;   // leading elements handled one by one (until 16-byte alignment)
+    uint64_t nvec;   // 16-byte vectors in the aligned body
+    uint64_t count;  // all elements
+};
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// bfloat16 is the upper half of a binary32: widening is a shift.
+__device__ __forceinline__ float bf16_low_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_high_to_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// binary32 -> bfloat16 bits, round to nearest even in integer arithmetic; a NaN
+// keeps sign and upper payload and gets its quiet bit set.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    uint32_t quiet = (u >> 16) | 0x0040u;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded;
+}
+
+// One 16-byte vector from each of N inputs -> one 16-byte result.
+template <int N, bool BF16>
+__device__ __forceinline__ u32x4 reduce_vectors(const u32x4 (&v)[N]) {
+    u32x4 o;
+    if (BF16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            float lo = bf16_low_to_f32(v[0][w]);
+            float hi = bf16_high_to_f32(v[0][w]);
+#pragma unroll
+            for (int r = 1; r < N; ++r) {
+                lo = lo + bf16_low_to_f32(v[r][w]);
+                hi = hi + bf16_high_to_f32(v[r][w]);
+            }
+            o[w] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+        }
+    } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            float acc = __uint_as_float(v[0][w]);
+#pragma unroll
+            for (int r = 1; r < N; ++r) acc = acc + __uint_as_float(v[r][w]);
+            o[w] = __float_as_uint(acc);
+        }
+    }
+    return o;
+}
+
+template <int N, bool BF16>
+__device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t i) {
+    if (BF16) {
+        float acc = __uint_as_float((uint32_t)((const uint16_t*)a.in[0])[i] << 16);
+#pragma unroll
+        for (int r = 1; r < N; ++r)
+            acc = acc + __uint_as_float((uint32_t)((const uint16_t*)a.in[r])[i] << 16);
+        ((uint16_t*)a.out)[i] = (uint16_t)f32_to_bf16_bits(acc);
+    } else {
+        float acc = ((const float*)a.in[0])[i];
+#pragma unroll
+        for (int r = 1; r < N; ++r) acc = acc + ((const float*)a.in[r])[i];
+        ((float*)a.out)[i] = acc;
+    }
+}
+
+template <int N, bool BF16, int UNROLL, bool NT>
+__global__ void reduce_n_kernel(ReduceArgs a) {
+    constexpr uint32_t kElemSize = BF16 ? 2 : 4;
+    constexpr uint32_t kVecElems = 16 / kElemSize;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nthreads = blockDim.x;
+    const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
+    const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
+
+    const u32x4* in[N];
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+        in[r] = (const u32x4*)((const char*)a.in[r] + a.head * kElemSize);
+    u32x4* out = (u32x4*)((char*)a.out + a.head * kElemSize);
+
+    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const uint64_t first = tile * tile_vecs;
+        if (first + tile_vecs <= a.nvec) {
+            u32x4 v[UNROLL][N];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int r = 0; r < N; ++r)
+                    v[u][r] = load16<NT>(in[r] + first + (uint64_t)u * nthreads + tid);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                store16<NT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, BF16>(v[u]));
+        } else {
+            // ragged last tile
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint64_t idx = first + (uint64_t)u * nthreads + tid;
+                if (idx < a.nvec) {
+                    u32x4 v[N];
+#pragma unroll
+                    for (int r = 0; r < N; ++r) v[r] = load16<NT>(in[r] + idx);
+                    store16<NT>(out + idx, reduce_vectors<N, BF16>(v));
+                }
+            }
+        }
+    }
+
+    // Elements outside the aligned body: [0, head) and [head + nvec*kVecElems, count).
+    const uint64_t body_end = a.head + a.nvec * kVecElems;
+    const uint64_t nscalar = a.head + (a.count - body_end);
+    for (uint64_t k = (uint64_t)blockIdx.x * nthreads + tid; k < nscalar;
+         k += (uint64_t)gridDim.x * nthreads) {
+        const uint64_t i = k < a.head ? k : body_end + (k - a.head);
+        reduce_one_element<N, BF16>(a, i);
+    }
+}
+
+template <int N, bool BF16, int UNROLL, bool NT>
+int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, hipStream_t stream) {
+    hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, NT>), dim3(grid), dim3(threads), 0, stream, a);
+    return (int)hipGetLastError();
+}
+
+template <int N, bool BF16>
+int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, bool nt,
+             hipStream_t stream) {
+    switch (unroll) {
+        case 1:
+            return nt ? launch_one<N, BF16, 1, true>(a, grid, threads, stream)
+                      : launch_one<N, BF16, 1, false>(a, grid, threads, stream);
+        case 2:
+            return nt ? launch_one<N, BF16, 2, true>(a, grid, threads, stream)
+                      : launch_one<N, BF16, 2, false>(a, grid, threads, stream);
+        default:
+            return nt ? launch_one<N, BF16, 4, true>(a, grid, threads, stream)
+                      : launch_one<N, BF16, 4, false>(a, grid, threads, stream);
+    }
+}
+
+template <bool BF16>
+int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, bool nt,
+                 hipStream_t stream) {
+    switch (n) {
+        case 1: return launch_n<1, BF16>(a, grid, threads, unroll, nt, stream);
+        case 2: return launch_n<2, BF16>(a, grid, threads, unroll, nt, stream);
+        case 3: return launch_n<3, BF16>(a, grid, threads, unroll, nt, stream);
+        case 4: return launch_n<4, BF16>(a, grid, threads, unroll, nt, stream);
+        case 5: return launch_n<5, BF16>(a, grid, threads, unroll, nt, stream);
+        case 6: return launch_n<6, BF16>(a, grid, threads, unroll, nt, stream);
+        case 7: return launch_n<7, BF16>(a, grid, threads, unroll, nt, stream);
+        default: return launch_n<8, BF16>(a, grid, threads, unroll, nt, stream);
+    }
+}
+
+}  // namespace
+
+namespace flex {
+
+int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int dtype,
+                    const LaunchShape& shape, void* stream) {
+    if (count == 0) return 0;
+    const size_t esize = dtype_size(dtype);
+    const size_t vec_elems = 16 / esize;
+    ReduceArgs a;
+    for (int r = 0; r < FLEX_MAX_RANKS; ++r) a.in[r] = r < n ? in[r] : nullptr;
+    a.out = out;
+    a.count = count;
+
+    // The 16-byte body needs every pointer at the same offset within a
+    // 16-byte line, and that offset a whole number of elements.
+    const uintptr_t mis = (uintptr_t)out & 15;
+    bool congruent = (mis % esize) == 0;
+    for (int r = 0; r < n; ++r) congruent = congruent && (((uintptr_t)in[r] & 15) == mis);
+    uint64_t head = count;
+    if (congruent) {
+        head = ((16 - mis) & 15) / esize;
+        if (head > count) head = count;
+    }
+    a.head = head;
+    a.nvec = (count - head) / vec_elems;
+
+    const uint32_t threads = shape.threads;
+    const uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : 4;
+    const uint64_t tile_vecs = (uint64_t)threads * unroll;
+    const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
+    const uint64_t nscalar = count - a.nvec * vec_elems;
+    const uint64_t scalar_blocks = (nscalar + threads - 1) / threads;
+    uint64_t grid = ntiles;
+    uint64_t resident = (uint64_t)shape.num_cus * (shape.waves_per_cu ? shape.waves_per_cu : 1) * 64 / threads;
+    if (resident == 0) resident = 1;
+    if (shape.waves_per_cu && grid > resident) grid = resident;
+    // one-by-one elements: enough blocks to spread them, but never more than a
+    // persistent grid's worth beyond the tiles
+    uint64_t sgrid = scalar_blocks < resident * 8 ? scalar_blocks : resident * 8;
+    if (grid < sgrid) grid = sgrid;
+    if (grid == 0) grid = 1;
+    if (grid > 0x7fffffffull) grid = 0x7fffffffull;
+
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == FLEX_BF16)
+        return launch_dtype<true>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal != 0, s);
+    return launch_dtype<false>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal != 0, s);
+}
+
+}  // namespace flex

@@ -1,0 +1,444 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on a real
+MI355X.  Integer/byte work (AllGather) and, because the summation order is
+fixed, the floating-point AllReduce too must match bit for bit: tolerance 0 ULP
+wherever the oracle's result is not a NaN; a NaN must come out as a NaN."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import collectives as oc
+from paper_2510_15882_amd import binding as fx
+from paper_2510_15882_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    fx.lib()
+    torch.cuda.set_device(0)
+    yield
+    torch.cuda.synchronize()
+
+
+class Comm:
+    def __init__(self, nranks=8, rank=0, max_bytes=64 << 20, **cfg_fields):
+        cfg = fx.flex_config_default()
+        for k, v in cfg_fields.items():
+            setattr(cfg, k, v)
+        self.h = fx.flex_comm_create(nranks, rank, max_bytes, cfg)
+
+    def __enter__(self):
+        return self.h
+
+    def __exit__(self, *a):
+        torch.cuda.synchronize()
+        fx.flex_comm_destroy(self.h)
+
+
+def assert_same_bits(got: torch.Tensor, want_bits: np.ndarray, what=""):
+    got_bits = wl.to_numpy_bits(got)
+    if got_bits.dtype == np.float32:
+        g, w = got_bits.view(np.uint32), want_bits.view(np.uint32)
+        nan = np.isnan(want_bits)
+        got_nan = np.isnan(got_bits)
+    else:
+        g, w = got_bits, want_bits
+        nan = ((w & 0x7F80) == 0x7F80) & ((w & 0x7F) != 0)
+        got_nan = ((g & 0x7F80) == 0x7F80) & ((g & 0x7F) != 0)
+    assert g.shape == w.shape, what
+    bad = (g != w) & ~nan
+    if bad.any():
+        i = int(np.flatnonzero(bad)[0])
+        raise AssertionError("%s: %d of %d elements differ, first at %d: got 0x%x want 0x%x"
+                             % (what, int(bad.sum()), g.size, i, int(g[i]), int(w[i])))
+    assert np.array_equal(nan, got_nan), what + ": NaN positions differ"
+
+
+def oracle_allreduce(bufs):
+    return oc.allreduce([wl.to_numpy_bits(b) for b in bufs])
+
+
+def oracle_allgather(slices):
+    return oc.allgather([wl.to_numpy_bits(b) for b in slices])
+
+
+COUNTS = [0, 1, 7, 8, 9, 2047, 2048, 2049, 65536, (1 << 20) + 3]
+
+
+# ------------------------------------------------------------ device path
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nranks", [1, 2, 3, 8])
+def test_allreduce_device_path_all_counts(dtype, nranks):
+    with Comm(nranks=nranks) as comm:
+        for count in COUNTS:
+            say("allreduce device", dtype, nranks, count)
+            bufs = [wl.random_bits(count, dtype, 11 * r + count % 97, DEV, finite_only=True) for r in range(nranks)]
+            # keep exponents within reach of each other so that roundings matter
+            bufs = [torch.ldexp(torch.frexp(b.float())[0], torch.tensor(r % 3, device=DEV)).to(dtype) for r, b in enumerate(bufs)]
+            out = torch.full((count + 8,), 7.0, dtype=dtype, device=DEV)
+            fx.flex_allreduce_local(comm, bufs, out, count=count)
+            torch.cuda.synchronize()
+            assert_same_bits(out[:count], oracle_allreduce(bufs), "count %d" % count)
+            assert torch.all(out[count:] == 7.0), "wrote past the end"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_allreduce_raw_bit_patterns_and_specials(dtype):
+    count = 300007
+    with Comm() as comm:
+        bufs = [wl.random_bits(count, dtype, 500 + r, DEV) for r in range(8)]   # NaN, inf, denormals included
+        out = torch.empty(count, dtype=dtype, device=DEV)
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), "raw bits")
+        # denormal inputs and sums stay denormal (no flushing)
+        tiny = torch.full((4099,), 1e-40, dtype=torch.float32, device=DEV).to(dtype)
+        bufs = [tiny * (r + 1) for r in range(8)]
+        out = torch.empty(4099, dtype=dtype, device=DEV)
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        want = oracle_allreduce(bufs)
+        assert want.view(np.uint32 if dtype == torch.float32 else np.uint16)[0] != 0
+        assert_same_bits(out, want, "denormals")
+        # signed zero: starts from rank 0's value
+        neg0 = torch.full((1000,), -0.0, dtype=dtype, device=DEV)
+        fx.flex_allreduce_local(comm, [neg0] * 8, out[:1000], count=1000)
+        torch.cuda.synchronize()
+        assert_same_bits(out[:1000], oracle_allreduce([neg0] * 8), "-0")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_allreduce_misaligned_pointers_and_in_place(dtype):
+    count = 100003
+    with Comm() as comm:
+        base = wl.make_rank_buffers(wl.config(0 if dtype == torch.float32 else 1), DEV, count=count + 64)
+        # same misalignment everywhere (vector body with a scalar head)
+        for off in (1, 3, 5):
+            bufs = [b[off:off + count] for b in base]
+            out_full = torch.zeros(count + 64, dtype=dtype, device=DEV)
+            out = out_full[off:off + count]
+            fx.flex_allreduce_local(comm, bufs, out)
+            torch.cuda.synchronize()
+            assert_same_bits(out, oracle_allreduce(bufs), "offset %d" % off)
+            assert out_full[:off].abs().sum() == 0 and out_full[off + count:].abs().sum() == 0
+        # different misalignment per rank (element-wise path)
+        bufs = [b[r:r + count] for r, b in enumerate(base)]
+        out = torch.zeros(count + 2, dtype=dtype, device=DEV)[2:]
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), "mixed offsets")
+        # in place: out is rank 3's buffer
+    with Comm(rank=3, max_host_units=10000) as comm:
+        for units in (0, 1200):
+            bufs = [b[:count].clone() for b in base]
+            want = oracle_allreduce(bufs)
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+            fx.flex_allreduce_local(comm, bufs, bufs[3])
+            torch.cuda.synchronize()
+            assert_same_bits(bufs[3], want, "in place units %d" % units)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nranks", [1, 2, 8])
+def test_allgather_device_path_all_counts(dtype, nranks):
+    with Comm(nranks=nranks) as comm:
+        for count in COUNTS:
+            say("allgather device", dtype, nranks, count)
+            slices = [wl.random_bits(count, dtype, 31 * r + count % 89, DEV) for r in range(nranks)]
+            out = torch.full((nranks * count + 8,), 7.0, dtype=dtype, device=DEV)
+            fx.flex_allgather_local(comm, slices, out, slice_count=count)
+            torch.cuda.synchronize()
+            want = oracle_allgather(slices)
+            assert wl.to_numpy_bits(out[:nranks * count]).tobytes() == want.tobytes(), count
+            assert torch.all(out[nranks * count:] == 7.0)
+
+
+def test_allgather_misaligned_and_in_place():
+    dtype = torch.bfloat16
+    count = 70001                       # odd: every destination slice lands on a different alignment
+    with Comm(rank=2, max_host_units=10000) as comm:
+        base = [wl.random_bits(count + 16, dtype, 700 + r, DEV) for r in range(8)]
+        slices = [b[r % 5:r % 5 + count] for r, b in enumerate(base)]
+        want = oracle_allgather(slices)
+        for units in (0, 700):
+            fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+            out = torch.zeros(8 * count + 3, dtype=dtype, device=DEV)[3:]
+            fx.flex_allgather_local(comm, slices, out)
+            torch.cuda.synchronize()
+            assert wl.to_numpy_bits(out).tobytes() == want.tobytes(), units
+            # in place: rank 2's slice already sits at its offset
+            out2 = torch.zeros(8 * count, dtype=dtype, device=DEV)
+            out2[2 * count:3 * count] = slices[2]
+            sl = list(slices)
+            sl[2] = out2[2 * count:3 * count]
+            fx.flex_allgather_local(comm, sl, out2)
+            torch.cuda.synchronize()
+            assert wl.to_numpy_bits(out2).tobytes() == want.tobytes(), ("in place", units)
+
+
+@pytest.mark.parametrize("threads,unroll,waves,nt", [
+    (64, 1, 0, 0), (128, 2, 0, 1), (256, 4, 0, 1), (512, 2, 8, 1), (1024, 4, 4, 0), (256, 1, 16, 1), (256, 8, 2, 1)])
+def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
+    count = (1 << 21) + 12345
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want_ar = oracle_allreduce(bufs)
+    want_ag = oracle_allgather(bufs)
+    with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
+              copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves, nontemporal=nt) as comm:
+        out = torch.empty(count, dtype=torch.bfloat16, device=DEV)
+        fx.flex_allreduce_local(comm, bufs, out)
+        out2 = torch.empty(8 * count, dtype=torch.bfloat16, device=DEV)
+        fx.flex_allgather_local(comm, bufs, out2)
+        torch.cuda.synchronize()
+        assert_same_bits(out, want_ar, "allreduce")
+        assert wl.to_numpy_bits(out2).tobytes() == want_ag.tobytes()
+
+
+# ------------------------------------------------- split over both paths
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype):
+    count = (1 << 20) + 3
+    w = wl.config(0) if dtype == torch.float32 else wl.config(2)
+    bufs = wl.make_rank_buffers(w, DEV, count=count)
+    want = oracle_allreduce(bufs)
+    for chunk, slots in ((64 << 10, 2), (4 << 20, 2), (256 << 10, 3)):
+        for rank in (0, 3, 7):
+            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk, num_slots=slots) as comm:
+                for units in (0, 1, 500, 1200, 2200, 10000):
+                    say("allreduce split", dtype, chunk, rank, units)
+                    fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+                    out = torch.zeros(count, dtype=dtype, device=DEV)
+                    fx.flex_allreduce_local(comm, bufs, out)
+                    torch.cuda.synchronize()
+                    assert_same_bits(out, want, "chunk %d rank %d units %d" % (chunk, rank, units))
+                    st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, dtype)
+                    assert st.last_split == fx.flex_partition(count, units, 10000, 2048, (64 << 10) // out.element_size())
+
+
+def test_allgather_bits_do_not_depend_on_split_chunk_or_rank():
+    dtype = torch.bfloat16
+    count = (1 << 19) + 5
+    slices = [wl.random_bits(count, dtype, 40 + r, DEV) for r in range(8)]
+    want = oracle_allgather(slices).tobytes()
+    for chunk in (64 << 10, 4 << 20):
+        for rank in (0, 5):
+            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk) as comm:
+                for units in (0, 1, 500, 2200, 10000):
+                    say("allgather split", chunk, rank, units)
+                    fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+                    out = torch.zeros(8 * count, dtype=dtype, device=DEV)
+                    fx.flex_allgather_local(comm, slices, out)
+                    torch.cuda.synchronize()
+                    assert wl.to_numpy_bits(out).tobytes() == want, (chunk, rank, units)
+
+
+def test_back_to_back_calls_on_one_stream_and_repeatability():
+    # many split calls queued without host synchronisation, staging slots and
+    # scratch reused every call: every output must carry the same bits
+    count = (1 << 20) + 2048 + 1
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want = oracle_allreduce(bufs)
+    stream = torch.cuda.Stream()
+    with Comm(chunk_bytes=128 << 10) as comm:
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 700)
+        outs = [torch.zeros(count, dtype=torch.bfloat16, device=DEV) for _ in range(50)]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for o in outs:
+                fx.flex_allreduce_local(comm, bufs, o, stream=stream)
+        stream.synchronize()
+        for k, o in enumerate(outs):
+            assert_same_bits(o, want, "call %d" % k)
+        fx.flex_evaluator_drain(comm)
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+        assert st.calls == 50 and st.split_calls == 50 and st.samples == 50 and st.blocking_reads == 0
+        assert st.last_time_s[0] > 0 and st.last_time_s[1] > 0
+
+
+# --------------------------------------------------------- full-size configs
+
+def test_config0_allreduce_f32_1MiB():
+    w = wl.config(0)
+    bufs = wl.make_rank_buffers(w, DEV)
+    with Comm() as comm:
+        out = torch.empty(w.count, dtype=w.dtype, device=DEV)
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), w.name)
+
+
+def test_config1_allgather_bf16_256MiB():
+    w = wl.config(1)
+    slices = wl.make_rank_buffers(w, DEV)
+    with Comm(max_bytes=w.bytes_per_rank) as comm:
+        out = torch.empty(8 * w.count, dtype=w.dtype, device=DEV)
+        fx.flex_allgather_local(comm, slices, out)
+        torch.cuda.synchronize()
+        assert wl.to_numpy_bits(out).tobytes() == oracle_allgather(slices).tobytes()
+
+
+def test_config2_allreduce_bf16_256MiB_split_sweep():
+    w = wl.config(2)
+    say("generating", w.name)
+    bufs = wl.make_rank_buffers(w, DEV)
+    want = oracle_allreduce(bufs)
+    with Comm(max_bytes=w.bytes_per_rank) as comm:
+        for units in (0, 500, 1200, 2200):
+            say("config2 units", units)
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+            out = torch.zeros(w.count, dtype=w.dtype, device=DEV)
+            fx.flex_allreduce_local(comm, bufs, out)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, "%s units %d" % (w.name, units))
+
+
+def sampled_windows(count, nwin=48, width=1 << 16, seed=5):
+    rng = np.random.default_rng(seed)
+    starts = [0, count - width] + [int(s) for s in rng.integers(0, count - width, nwin)]
+    return [(s, s + width) for s in starts]
+
+
+def test_config3_largest_sweep_point_sampled():
+    # 1024 MiB per rank: the oracle checks sampled windows (first, last, random)
+    w = [x for x in wl.sweep_workloads() if x.count == 512 * wl.MIB]
+    ar = [x for x in w if x.collective == "allreduce"][0]
+    say("generating", ar.name)
+    bufs = wl.make_rank_buffers(ar, DEV)
+    with Comm(max_bytes=ar.bytes_per_rank) as comm:
+        out = torch.zeros(ar.count, dtype=ar.dtype, device=DEV)
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 100)
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        split = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, ar.count, ar.dtype).last_split
+        wins = sampled_windows(ar.count) + [(split - 4096, split + 4096)]
+        for a, b in wins:
+            assert_same_bits(out[a:b], oracle_allreduce([x[a:b] for x in bufs]), "window %d" % a)
+        del out
+        ag_out = torch.zeros(8 * ar.count, dtype=ar.dtype, device=DEV)
+        fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, 100)
+        fx.flex_allgather_local(comm, bufs, ag_out)
+        torch.cuda.synchronize()
+        for r in range(8):
+            for a, b in sampled_windows(ar.count, nwin=8, seed=r) + [(split - 4096, split + 4096)]:
+                assert torch.equal(ag_out[r * ar.count + a:r * ar.count + b].view(torch.int16),
+                                   bufs[r][a:b].view(torch.int16)), (r, a)
+
+
+def test_config4_prefill_allreduce_adaptive_50_calls():
+    w = wl.config(4)
+    say("generating", w.name)
+    bufs = wl.make_rank_buffers(w, DEV)
+    want = oracle_allreduce(bufs)
+    with Comm(max_bytes=w.bytes_per_rank) as comm:
+        out = torch.zeros(w.count, dtype=w.dtype, device=DEV)
+        res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
+        say("tune:", res.as_dict())
+        torch.cuda.synchronize()
+        assert_same_bits(out, want, "after tune")
+        assert sum(res.shares) == 10000 and res.path_bw[0] > 0
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
+        outs = [torch.zeros(w.count, dtype=w.dtype, device=DEV) for _ in range(2)]
+        for k in range(50):
+            fx.flex_allreduce_local(comm, bufs, outs[k % 2])
+        torch.cuda.synchronize()
+        assert_same_bits(outs[0], want, "call 48")
+        assert_same_bits(outs[1], want, "call 49")
+        fx.flex_evaluator_drain(comm)
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w.count, w.dtype)
+        say("stats:", st.as_dict())
+        assert st.balancer.npaths == 2 and sum(st.balancer.shares) == 10000
+        assert st.balancer.stage == fx.FLEX_STAGE_RUNTIME
+
+
+# ------------------------------------------------------ balancer on hardware
+
+def test_tune_then_adaptive_stays_exact_and_balanced():
+    count = 16 * wl.MIB        # 32 MiB per rank, bf16
+    bufs = wl.make_rank_buffers(wl.config(1), DEV, count=count)
+    want_ag = oracle_allgather(bufs).tobytes()
+    want_ar = oracle_allreduce(bufs)
+    with Comm() as comm:
+        out_ag = torch.zeros(8 * count, dtype=torch.bfloat16, device=DEV)
+        out_ar = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+        for coll, out in ((fx.FLEX_ALLGATHER, out_ag), (fx.FLEX_ALLREDUCE, out_ar)):
+            res = fx.flex_comm_tune(comm, coll, bufs, out)
+            say("tune", coll, res.as_dict())
+            assert sum(res.shares) == 10000 and res.iterations <= 100
+            assert res.initial_shares[1] == int(10000 * res.path_bw[1] / (res.path_bw[0] + res.path_bw[1]))
+            if res.active_mask & 2:
+                t = res.path_time_s
+                # Algorithm 1 stopped either balanced or at the iteration cap
+                assert res.iterations == 100 or abs(t[1] - t[0]) / min(t[0], t[1]) < 0.05 + 1e-9
+            else:
+                assert res.shares[1] == 0
+            fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
+        for k in range(35):
+            fx.flex_allgather_local(comm, bufs, out_ag)
+            fx.flex_allreduce_local(comm, bufs, out_ar)
+        torch.cuda.synchronize()
+        assert wl.to_numpy_bits(out_ag).tobytes() == want_ag
+        assert_same_bits(out_ar, want_ar, "adaptive allreduce")
+        fx.flex_evaluator_drain(comm)
+        for coll in (fx.FLEX_ALLGATHER, fx.FLEX_ALLREDUCE):
+            st = fx.flex_get_stats(comm, coll, count, torch.bfloat16)
+            say("stats", coll, st.as_dict())
+            assert sum(st.balancer.shares) == 10000
+            assert st.balancer.adjustments <= 3           # at most one move per 10-call window
+        # a size class that was never tuned borrows the nearest tuned one
+        half = [b[:count // 2] for b in bufs]
+        fx.flex_allreduce_local(comm, half, out_ar[:count // 2], count=count // 2)
+        torch.cuda.synchronize()
+        assert_same_bits(out_ar[:count // 2], oracle_allreduce(half), "borrowed class")
+
+
+# ------------------------------------------------------------ error handling
+
+def test_invalid_arguments_are_rejected_without_enqueueing():
+    bufs = wl.make_rank_buffers(wl.config(0), DEV, count=4096)
+    out = torch.zeros(4096, dtype=torch.float32, device=DEV)
+    L = fx.lib()
+    with pytest.raises(fx.FlexError) as e:
+        fx.flex_comm_create(9, 0, 1 << 20)
+    assert e.value.status == fx.FLEX_ERR_INVALID_ARG
+    with pytest.raises(fx.FlexError):
+        fx.flex_comm_create(8, 8, 1 << 20)
+    with Comm(max_bytes=4096 * 4) as comm:
+        ptrs = fx._pointer_array(bufs)
+        s = fx._stream_handle(None)
+        assert L.flex_allreduce_local(comm, ptrs, out.data_ptr(), 4097, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_ERR_INVALID_ARG
+        assert "max_bytes" in fx.flex_last_error()
+        assert L.flex_allreduce_local(comm, ptrs, out.data_ptr(), 4096, 7, fx.FLEX_SUM, s) == fx.FLEX_ERR_UNSUPPORTED
+        assert L.flex_allreduce_local(comm, ptrs, out.data_ptr(), 4096, fx.FLEX_F32, 3, s) == fx.FLEX_ERR_UNSUPPORTED
+        assert L.flex_allreduce_local(comm, ptrs, None, 4096, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_ERR_INVALID_ARG
+        assert L.flex_allreduce_local(comm, None, out.data_ptr(), 4096, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_ERR_INVALID_ARG
+        assert L.flex_allreduce_local(None, ptrs, out.data_ptr(), 4096, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_ERR_INVALID_ARG
+        bad = fx._pointer_array(bufs)
+        bad[5] = None
+        assert L.flex_allgather_local(comm, bad, out.data_ptr(), 512, fx.FLEX_F32, s) == fx.FLEX_ERR_INVALID_ARG
+        odd = fx._pointer_array(bufs)
+        odd[1] = bufs[1].data_ptr() + 2
+        assert L.flex_allreduce_local(comm, odd, out.data_ptr(), 16, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_ERR_INVALID_ARG
+        with pytest.raises(fx.FlexError):
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 2501)
+        with pytest.raises(fx.FlexError):
+            fx.flex_set_split(comm, 2, fx.FLEX_SPLIT_STATIC, 0)
+        torch.cuda.synchronize()
+        assert out.abs().sum() == 0          # nothing ran
+        # count 0 is fine and does nothing
+        assert L.flex_allreduce_local(comm, ptrs, None, 0, fx.FLEX_F32, fx.FLEX_SUM, s) == fx.FLEX_OK
+        # and the communicator still works after all the rejected calls
+        fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), "after errors")
