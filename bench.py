@@ -83,7 +83,8 @@ def main():
     ap.add_argument("--copy-threads", type=int, default=0)
     ap.add_argument("--copy-unroll", type=int, default=0)
     ap.add_argument("--copy-waves", type=int, default=0)
-    ap.add_argument("--nontemporal", type=int, default=1)
+    ap.add_argument("--reduce-nt", type=int, default=-1)
+    ap.add_argument("--copy-nt", type=int, default=-1)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is the single-GPU local share; it runs on exactly one GPU "
@@ -110,7 +111,10 @@ def main():
     cfg = fx.flex_config_default()
     cfg.reduce_threads, cfg.reduce_unroll, cfg.reduce_waves_per_cu = args.reduce_threads, args.reduce_unroll, args.reduce_waves
     cfg.copy_threads, cfg.copy_unroll, cfg.copy_waves_per_cu = args.copy_threads, args.copy_unroll, args.copy_waves
-    cfg.nontemporal = args.nontemporal
+    if args.reduce_nt >= 0:
+        cfg.reduce_nontemporal = args.reduce_nt
+    if args.copy_nt >= 0:
+        cfg.copy_nontemporal = args.copy_nt
     comm = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -209,9 +213,9 @@ def main():
         "config": {"workload": "configs[2] AllReduce bf16 8 ranks x 256 MiB (fp32 accumulate) + configs[1] "
                                "AllGather bf16 8 x 32 MiB -> 256 MiB, one call each per step",
                    "mode": args.mode, "nranks": N, "algorithmic_bytes_per_step": ar_bytes + ag_bytes,
-                   "launch": {k: getattr(cfg, k) for k in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu",
+                   "launch (0 = library default)": {k: getattr(cfg, k) for k in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu",
                                                             "copy_threads", "copy_unroll", "copy_waves_per_cu",
-                                                            "nontemporal")}},
+                                                            "reduce_nontemporal", "copy_nontemporal")}},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": roofline,
         "allreduce": {"ms_median": median(ar_ms), "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,

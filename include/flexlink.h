@@ -184,8 +184,8 @@ typedef struct flex_config {
     uint32_t copy_threads;
     uint32_t copy_unroll;        /* 1, 2, 4 or 8 */
     uint32_t copy_waves_per_cu;
-    uint32_t nontemporal;        /* 1 = mark streaming loads/stores non-temporal (default), 0 = plain */
-    uint32_t reserved;
+    uint32_t reduce_nontemporal; /* streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores */
+    uint32_t copy_nontemporal;   /* same for the copy kernel */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

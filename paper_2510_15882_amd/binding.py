@@ -55,7 +55,7 @@ class Config(_Struct):
                 ("split_align_elems", u32), ("min_split_bytes", u64), ("tune_reps", u32),
                 ("probe_units", u32), ("reduce_threads", u32), ("reduce_unroll", u32),
                 ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
-                ("copy_waves_per_cu", u32), ("nontemporal", u32), ("reserved", u32),
+                ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("balancer", BalancerCfg)]
 
 

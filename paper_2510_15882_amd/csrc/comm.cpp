@@ -452,13 +452,19 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->min_split_bytes = 64u << 10;
     cfg->tune_reps = 5;
     cfg->probe_units = 200;
-    cfg->reduce_threads = 256;
-    cfg->reduce_unroll = 2;
+    // Launch shapes found best on MI355X for the 8 x 256 MiB AllReduce followed by
+    // the 8 x 32 MiB AllGather: one wavefront per workgroup, one 16-byte vector
+    // per lane and input, one workgroup per tile; the reduce streams its loads
+    // (non-temporal) and leaves its stores to the write-back path, the copy
+    // streams both.
+    cfg->reduce_threads = 64;
+    cfg->reduce_unroll = 1;
     cfg->reduce_waves_per_cu = 0;
-    cfg->copy_threads = 256;
-    cfg->copy_unroll = 4;
+    cfg->copy_threads = 64;
+    cfg->copy_unroll = 1;
     cfg->copy_waves_per_cu = 0;
-    cfg->nontemporal = 1;
+    cfg->reduce_nontemporal = 1;
+    cfg->copy_nontemporal = 3;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -511,8 +517,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.nontemporal, (uint32_t)cus};
-    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.nontemporal, (uint32_t)cus};
+    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal, (uint32_t)cus};
+    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus};
 
     // Side streams at the default priority.
     CREATE_TRY(hipStreamCreateWithFlags(&m->s_d2h, hipStreamNonBlocking));

@@ -55,7 +55,7 @@ __device__ void copy_granules(const char* s, char* d, uint64_t bytes) {
     }
 }
 
-template <int UNROLL, bool NT>
+template <int UNROLL, bool LDNT, bool STNT>
 __global__ void gather_copy_kernel(CopyArgs a) {
     const int r = blockIdx.y;
     const char* s = (const char*)a.src[r];
@@ -90,13 +90,13 @@ __global__ void gather_copy_kernel(CopyArgs a) {
         if (first + tile_vecs <= nvec) {
             u32x4 v[UNROLL];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) v[u] = load16<NT>(in + first + (uint64_t)u * nthreads + tid);
+            for (int u = 0; u < UNROLL; ++u) v[u] = load16<LDNT>(in + first + (uint64_t)u * nthreads + tid);
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) store16<NT>(out + first + (uint64_t)u * nthreads + tid, v[u]);
+            for (int u = 0; u < UNROLL; ++u) store16<STNT>(out + first + (uint64_t)u * nthreads + tid, v[u]);
         } else {
             for (int u = 0; u < UNROLL; ++u) {
                 const uint64_t idx = first + (uint64_t)u * nthreads + tid;
-                if (idx < nvec) store16<NT>(out + idx, load16<NT>(in + idx));
+                if (idx < nvec) store16<STNT>(out + idx, load16<LDNT>(in + idx));
             }
         }
     }
@@ -112,9 +112,14 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     }
 }
 
-template <int UNROLL, bool NT>
-int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, hipStream_t stream) {
-    hipLaunchKernelGGL((gather_copy_kernel<UNROLL, NT>), grid, dim3(threads), 0, stream, a);
+template <int UNROLL>
+int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
+    switch (nt & 3u) {
+        case 0: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, false>), grid, dim3(threads), 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, false>), grid, dim3(threads), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, true>), grid, dim3(threads), 0, stream, a); break;
+        default: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, true>), grid, dim3(threads), 0, stream, a); break;
+    }
     return (int)hipGetLastError();
 }
 
@@ -148,12 +153,11 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     if (gx > 0x7fffffffull) gx = 0x7fffffffull;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;
-    const bool nt = shape.nontemporal != 0;
     switch (unroll) {
-        case 1: return nt ? launch_one<1, true>(a, grid, threads, s) : launch_one<1, false>(a, grid, threads, s);
-        case 2: return nt ? launch_one<2, true>(a, grid, threads, s) : launch_one<2, false>(a, grid, threads, s);
-        case 8: return nt ? launch_one<8, true>(a, grid, threads, s) : launch_one<8, false>(a, grid, threads, s);
-        default: return nt ? launch_one<4, true>(a, grid, threads, s) : launch_one<4, false>(a, grid, threads, s);
+        case 1: return launch_one<1>(a, grid, threads, shape.nontemporal, s);
+        case 2: return launch_one<2>(a, grid, threads, shape.nontemporal, s);
+        case 8: return launch_one<8>(a, grid, threads, shape.nontemporal, s);
+        default: return launch_one<4>(a, grid, threads, shape.nontemporal, s);
     }
 }
 

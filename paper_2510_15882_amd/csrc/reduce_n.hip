@@ -97,7 +97,7 @@ __device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t
     }
 }
 
-template <int N, bool BF16, int UNROLL, bool NT>
+template <int N, bool BF16, int UNROLL, bool LDNT, bool STNT>
 __global__ void reduce_n_kernel(ReduceArgs a) {
     constexpr uint32_t kElemSize = BF16 ? 2 : 4;
     constexpr uint32_t kVecElems = 16 / kElemSize;
@@ -120,10 +120,10 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
             for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
                 for (int r = 0; r < N; ++r)
-                    v[u][r] = load16<NT>(in[r] + first + (uint64_t)u * nthreads + tid);
+                    v[u][r] = load16<LDNT>(in[r] + first + (uint64_t)u * nthreads + tid);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
-                store16<NT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, BF16>(v[u]));
+                store16<STNT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, BF16>(v[u]));
         } else {
             // ragged last tile
             for (int u = 0; u < UNROLL; ++u) {
@@ -131,8 +131,8 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
                 if (idx < a.nvec) {
                     u32x4 v[N];
 #pragma unroll
-                    for (int r = 0; r < N; ++r) v[r] = load16<NT>(in[r] + idx);
-                    store16<NT>(out + idx, reduce_vectors<N, BF16>(v));
+                    for (int r = 0; r < N; ++r) v[r] = load16<LDNT>(in[r] + idx);
+                    store16<STNT>(out + idx, reduce_vectors<N, BF16>(v));
                 }
             }
         }
@@ -148,30 +148,29 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     }
 }
 
-template <int N, bool BF16, int UNROLL, bool NT>
-int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, hipStream_t stream) {
-    hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, NT>), dim3(grid), dim3(threads), 0, stream, a);
+template <int N, bool BF16, int UNROLL>
+int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
+    switch (nt & 3u) {
+        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, false, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+        default: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+    }
     return (int)hipGetLastError();
 }
 
 template <int N, bool BF16>
-int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, bool nt,
+int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
              hipStream_t stream) {
     switch (unroll) {
-        case 1:
-            return nt ? launch_one<N, BF16, 1, true>(a, grid, threads, stream)
-                      : launch_one<N, BF16, 1, false>(a, grid, threads, stream);
-        case 2:
-            return nt ? launch_one<N, BF16, 2, true>(a, grid, threads, stream)
-                      : launch_one<N, BF16, 2, false>(a, grid, threads, stream);
-        default:
-            return nt ? launch_one<N, BF16, 4, true>(a, grid, threads, stream)
-                      : launch_one<N, BF16, 4, false>(a, grid, threads, stream);
+        case 1: return launch_one<N, BF16, 1>(a, grid, threads, nt, stream);
+        case 2: return launch_one<N, BF16, 2>(a, grid, threads, nt, stream);
+        default: return launch_one<N, BF16, 4>(a, grid, threads, nt, stream);
     }
 }
 
 template <bool BF16>
-int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, bool nt,
+int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
                  hipStream_t stream) {
     switch (n) {
         case 1: return launch_n<1, BF16>(a, grid, threads, unroll, nt, stream);
@@ -231,8 +230,8 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
 
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)
-        return launch_dtype<true>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal != 0, s);
-    return launch_dtype<false>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal != 0, s);
+        return launch_dtype<true>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+    return launch_dtype<false>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
 }
 
 }  // namespace flex

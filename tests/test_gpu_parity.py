@@ -188,14 +188,15 @@ def test_allgather_misaligned_and_in_place():
 
 
 @pytest.mark.parametrize("threads,unroll,waves,nt", [
-    (64, 1, 0, 0), (128, 2, 0, 1), (256, 4, 0, 1), (512, 2, 8, 1), (1024, 4, 4, 0), (256, 1, 16, 1), (256, 8, 2, 1)])
+    (64, 1, 0, 0), (128, 2, 0, 1), (256, 4, 0, 2), (512, 2, 8, 3), (1024, 4, 4, 0), (256, 1, 16, 1), (256, 8, 2, 3)])
 def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
     count = (1 << 21) + 12345
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want_ar = oracle_allreduce(bufs)
     want_ag = oracle_allgather(bufs)
     with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
-              copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves, nontemporal=nt) as comm:
+              copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves, reduce_nontemporal=nt,
+              copy_nontemporal=nt) as comm:
         out = torch.empty(count, dtype=torch.bfloat16, device=DEV)
         fx.flex_allreduce_local(comm, bufs, out)
         out2 = torch.empty(8 * count, dtype=torch.bfloat16, device=DEV)
