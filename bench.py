@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--mode", default="adaptive",
                     help="adaptive (tuned balancer) | device (host share 0) | static:UNITS (of 10000)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only launch a plain copy of known size (1-rank AllGather of 1 GiB, 10 launches): the "
+                         "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed device-only / static-split legs")
     ap.add_argument("--reduce-threads", type=int, default=0)
     ap.add_argument("--reduce-unroll", type=int, default=0)
@@ -98,6 +101,19 @@ def main():
     fx.lib()
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.pmc_calibration:
+        n = 1 << 29                                   # 512 Mi bf16 = 1 GiB
+        src = torch.empty(n, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        comm = fx.flex_comm_create(1, 0, 2 * n)
+        for _ in range(10):
+            fx.flex_allgather_local(comm, [src], dst)
+        torch.cuda.synchronize()
+        assert torch.equal(src.view(torch.int16), dst.view(torch.int16))
+        fx.flex_comm_destroy(comm)
+        print(json.dumps({"calibration": "gather_copy_kernel, 1 rank, 10 launches",
+                          "read_bytes_per_launch": 2 * n, "write_bytes_per_launch": 2 * n}))
+        return
     w_ar, w_ag = wl.config(2), wl.config(1)
     N = 8
     log("generating inputs on the GPU ...")
