@@ -167,9 +167,18 @@ int flex_partition(uint64_t count, uint32_t host_units, uint32_t share_total,
 /* ------------------------------------------------------------------------
  * Communicator (paper: Section "Communicator").
  * ---------------------------------------------------------------------- */
+enum flex_host_engine {
+    FLEX_ENGINE_KERNEL = 0, /* both stages of the host path are small HIP kernels that write to / read
+                               from the pinned buffer over PCIe; for AllReduce the second stage is the
+                               reduce kernel itself, reading the peers straight from pinned memory */
+    FLEX_ENGINE_SDMA = 1    /* both stages are hipMemcpyAsync copies (DMA engines); AllReduce then
+                               reduces from a device scratch buffer */
+};
+
 typedef struct flex_config {
-    uint64_t chunk_bytes;        /* size of one pinned transit buffer (paper: 4 MB; default 4 MiB) */
-    uint32_t num_slots;          /* transit buffers in the ring; 2 = the paper's double buffering */
+    uint64_t chunk_bytes;        /* transit buffer bytes per peer and pipeline step (paper: 4 MB; default
+                                    4 MiB); one pinned slot holds (nranks-1) * chunk_bytes */
+    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering */
     uint32_t max_host_units;     /* largest host share a call may use; sizes the device scratch
                                     (default 2500 = 25 %) */
     uint32_t split_align_elems;  /* alignment of the cut, elements (default 2048) */
@@ -186,6 +195,12 @@ typedef struct flex_config {
     uint32_t copy_waves_per_cu;
     uint32_t reduce_nontemporal; /* streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores */
     uint32_t copy_nontemporal;   /* same for the copy kernel */
+    uint32_t host_engine;        /* flex_host_engine (default FLEX_ENGINE_KERNEL) */
+    uint32_t host_blocks;        /* FLEX_ENGINE_KERNEL: workgroups (of 256 threads) each host-path kernel may
+                                    occupy (default 64) */
+    uint32_t pipeline_depth;     /* a host part shorter than pipeline_depth * chunk_bytes per peer is still
+                                    cut into up to this many steps so that the two stages overlap (default 4) */
+    uint32_t min_step_bytes;     /* ... but no step is shorter than this per peer (default 256 KiB) */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 
@@ -224,9 +239,10 @@ int flex_config_default(flex_config_t* cfg);
  *                       buffer is local and never takes the host path.
  *   max_bytes_per_rank  largest per-rank message any later call will pass.
  *   cfg                 host pointer or NULL for defaults.
- * Allocates, once: num_slots pinned buffers of chunk_bytes, a device scratch of
- * (nranks-1) * ceil(max_bytes_per_rank * max_host_units / share_total) bytes
- * (rounded up), two side streams at default priority, and an event ring.
+ * Allocates, once: num_slots pinned slots of (nranks-1) * chunk_bytes, two side
+ * streams at default priority, an event ring and, for FLEX_ENGINE_SDMA only, a
+ * device scratch of (nranks-1) * ceil(max_bytes_per_rank * max_host_units /
+ * share_total) bytes (rounded up).
  * Nothing is allocated per call afterwards.
  * Errors: INVALID_ARG, NOMEM, HIP. */
 int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_per_rank,
@@ -252,9 +268,9 @@ int flex_comm_destroy(flex_comm_t* comm);
  * (bfloat16: round-to-nearest-even; a NaN result is some quiet NaN).  The bits
  * of out do not depend on the split, the chunk size, `rank` or the launch
  * shape.  Elements [0, split) are reduced by the device path on hip_stream;
- * peers' elements [split, count) travel through the pinned transit buffers into
- * device scratch on the side streams and are reduced there, in the same rank
- * order, together with the local rank's elements read in place.
+ * peers' elements [split, count) travel through the pinned transit buffers on
+ * the side streams and are reduced there, in the same rank order, together
+ * with the local rank's elements read in place.
  * Pointers need no particular alignment (16-byte aligned ones take the fast
  * path).  out may be the same buffer as rank_bufs[rank]; any other overlap
  * between out and an input is undefined.

@@ -91,7 +91,8 @@ struct flex_comm {
     int nranks = 0, rank = 0;
     size_t max_bytes = 0;
     flex_config_t cfg;
-    flex::LaunchShape reduce_shape, copy_shape;
+    flex::LaunchShape reduce_shape, copy_shape;            // device path
+    flex::LaunchShape host_reduce_shape, host_copy_shape;  // host path (kernel engine): few workgroups
 
     hipStream_t s_d2h = nullptr, s_h2d = nullptr;
     std::vector<void*> pinned;
@@ -109,22 +110,92 @@ struct flex_comm {
     CollState coll[2];
 
     // ---- host-staged path --------------------------------------------------
-    // Enqueue src -> pinned slot -> dst in chunks.  A slot is refilled only
-    // after the H2D copy that drained it (ev_empty), and drained only after
-    // the D2H copy that filled it (ev_full); the D2H of one chunk overlaps the
-    // H2D of the previous one because they sit on different streams and slots.
-    int stage(const char* src, char* dst, size_t bytes) {
+    // What the consumer stage does with a step once it sits in the pinned slot.
+    struct HostJob {
+        int npeers = 0;
+        const char* peer_src[FLEX_MAX_RANKS];  // start of each peer's host part (device memory)
+        // AllGather: where each peer's host part goes
+        char* peer_dst[FLEX_MAX_RANKS];
+        // AllReduce: reduce in rank order into out_tail; the local rank's part is read in place
+        bool reduce = false;
+        int dtype = 0;
+        int local_index = 0;  // position of the local rank among the nranks inputs
+        const char* local_src = nullptr;
+        char* out_tail = nullptr;
+    };
+
+    // Move `bytes` bytes per peer through the ring of pinned slots, step by
+    // step: producer stage (device -> pinned slot) on s_d2h, consumer stage
+    // (pinned slot -> device) on s_h2d.  A slot is refilled only after the
+    // consumer that drained it (ev_empty) and drained only after the producer
+    // that filled it (ev_full), so the producer of one step overlaps the
+    // consumer of the previous one: PCIe carries both directions at once.  The
+    // slot of a step is its sequence number modulo the ring size, counted since
+    // the communicator was created.
+    int host_path(const HostJob& job, size_t bytes) {
         const size_t nslots = pinned.size();
-        for (size_t off = 0; off < bytes; off += cfg.chunk_bytes) {
-            const size_t n = std::min<size_t>(cfg.chunk_bytes, bytes - off);
+        const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
+        // even steps: no short remainder step, and a short host part is still cut
+        // into a few steps so that the two stages overlap
+        size_t nsteps = (bytes + cfg.chunk_bytes - 1) / cfg.chunk_bytes;
+        size_t want = std::min<size_t>(cfg.pipeline_depth, bytes / std::max<size_t>(cfg.min_step_bytes, 1));
+        nsteps = std::max<size_t>(std::max(nsteps, want), 1);
+        size_t step = ((bytes + nsteps - 1) / nsteps + 255) / 256 * 256;
+        const bool kernels = cfg.host_engine == FLEX_ENGINE_KERNEL;
+
+        for (size_t off = 0; off < bytes; off += step) {
+            const size_t n = std::min(step, bytes - off);
             const size_t slot = chunk_seq % nslots;
+            char* base = (char*)pinned[slot];
+            const void* up_src[FLEX_MAX_RANKS];
+            void* up_dst[FLEX_MAX_RANKS];
+            uint64_t nn[FLEX_MAX_RANKS];
+            for (int j = 0; j < job.npeers; ++j) {
+                up_src[j] = job.peer_src[j] + off;
+                up_dst[j] = base + (size_t)j * cfg.chunk_bytes;
+                nn[j] = n;
+            }
+            // producer stage
             if (chunk_seq >= nslots) HIP_TRY(hipStreamWaitEvent(s_d2h, ev_empty[slot], 0));
-            HIP_TRY(hipMemcpyAsync(pinned[slot], src + off, n, hipMemcpyDeviceToHost, s_d2h));
+            if (kernels) {
+                LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, host_copy_shape, s_d2h));
+            } else {
+                for (int j = 0; j < job.npeers; ++j)
+                    HIP_TRY(hipMemcpyAsync(up_dst[j], up_src[j], n, hipMemcpyDeviceToHost, s_d2h));
+            }
             HIP_TRY(hipEventRecord(ev_full[slot], s_d2h));
+            // consumer stage
             HIP_TRY(hipStreamWaitEvent(s_h2d, ev_full[slot], 0));
-            HIP_TRY(hipMemcpyAsync(dst + off, pinned[slot], n, hipMemcpyHostToDevice, s_h2d));
+            if (kernels && job.reduce) {
+                // the reduce kernel reads the peers straight from the pinned slot
+                const void* in[FLEX_MAX_RANKS];
+                int j = 0;
+                for (int r = 0; r < nranks; ++r)
+                    in[r] = (r == job.local_index) ? (const void*)(job.local_src + off) : up_dst[j++];
+                LAUNCH_TRY(flex::launch_reduce_n(in, nranks, job.out_tail + off, n / es, job.dtype,
+                                                 host_reduce_shape, s_h2d));
+            } else if (kernels) {
+                const void* dn_src[FLEX_MAX_RANKS];
+                void* dn_dst[FLEX_MAX_RANKS];
+                for (int j = 0; j < job.npeers; ++j) {
+                    dn_src[j] = up_dst[j];
+                    dn_dst[j] = job.peer_dst[j] + off;
+                }
+                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, host_copy_shape, s_h2d));
+            } else {
+                for (int j = 0; j < job.npeers; ++j)
+                    HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, s_h2d));
+            }
             HIP_TRY(hipEventRecord(ev_empty[slot], s_h2d));
             ++chunk_seq;
+        }
+        if (!kernels && job.reduce) {
+            // DMA engine: the peers' parts now sit in device scratch (peer_dst)
+            const void* in[FLEX_MAX_RANKS];
+            int j = 0;
+            for (int r = 0; r < nranks; ++r)
+                in[r] = (r == job.local_index) ? (const void*)job.local_src : (const void*)job.peer_dst[j++];
+            LAUNCH_TRY(flex::launch_reduce_n(in, nranks, job.out_tail, bytes / es, job.dtype, reduce_shape, s_h2d));
         }
         return FLEX_OK;
     }
@@ -302,7 +373,7 @@ int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int d
         LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, count, dtype, reduce_shape, stream));
         return FLEX_OK;
     }
-    if (host_count * es > scratch_stride)
+    if (cfg.host_engine == FLEX_ENGINE_SDMA && host_count * es > scratch_stride)
         return flex::fail(FLEX_ERR_INVALID_ARG,
                           "flex_allreduce_local: host part of %zu bytes exceeds the scratch sized by "
                           "max_host_units (%zu bytes per peer)",
@@ -326,24 +397,22 @@ int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int d
     if (split > 0) LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, split, dtype, reduce_shape, stream));
     HIP_TRY(hipEventRecord(rec->dev_done, stream));
 
-    // host path: every peer's tail goes device -> pinned -> device scratch ...
-    const void* tail_in[FLEX_MAX_RANKS];
-    int peer = 0;
+    // host path: every peer's tail goes device -> pinned slot -> device and is
+    // reduced in the same rank order; the local contribution never leaves HBM
+    HostJob job;
+    job.reduce = true;
+    job.dtype = dtype;
+    job.local_index = rank;
+    job.local_src = (const char*)bufs[rank] + split * es;
+    job.out_tail = (char*)out + split * es;
     for (int r = 0; r < nranks; ++r) {
-        const char* src = (const char*)bufs[r] + split * es;
-        if (r == rank) {
-            tail_in[r] = src;  // the local contribution never leaves the device
-            continue;
-        }
-        char* dst = scratch + (size_t)peer * scratch_stride;
-        st = stage(src, dst, host_count * es);
-        if (st) return st;
-        tail_in[r] = dst;
-        ++peer;
+        if (r == rank) continue;
+        job.peer_src[job.npeers] = (const char*)bufs[r] + split * es;
+        job.peer_dst[job.npeers] = scratch ? scratch + (size_t)job.npeers * scratch_stride : nullptr;
+        ++job.npeers;
     }
-    // ... and is reduced there in the same rank order
-    LAUNCH_TRY(flex::launch_reduce_n(tail_in, nranks, (char*)out + split * es, host_count, dtype,
-                                     reduce_shape, s_h2d));
+    st = host_path(job, host_count * es);
+    if (st) return st;
     HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
 
     // join
@@ -402,11 +471,15 @@ int flex_comm::allgather(const void* const* slices, void* out, size_t count, int
     LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
     HIP_TRY(hipEventRecord(rec->dev_done, stream));
 
+    HostJob job;
     for (int r = 0; r < nranks; ++r) {
         if (r == rank) continue;
-        st = stage((const char*)slices[r] + split * es, (char*)dst[r] + split * es, host_bytes);
-        if (st) return st;
+        job.peer_src[job.npeers] = (const char*)slices[r] + split * es;
+        job.peer_dst[job.npeers] = (char*)dst[r] + split * es;
+        ++job.npeers;
     }
+    st = host_path(job, host_bytes);
+    if (st) return st;
     HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
     HIP_TRY(hipStreamWaitEvent(stream, rec->host_done, 0));
     return FLEX_OK;
@@ -465,6 +538,10 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->copy_waves_per_cu = 0;
     cfg->reduce_nontemporal = 1;
     cfg->copy_nontemporal = 3;
+    cfg->host_engine = FLEX_ENGINE_KERNEL;
+    cfg->host_blocks = 64;
+    cfg->pipeline_depth = 4;
+    cfg->min_step_bytes = 256u << 10;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -490,7 +567,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
         if (!c.copy_unroll) c.copy_unroll = d.copy_unroll;
     }
     const flex_balancer_cfg_t& b = c.balancer;
-    if (c.chunk_bytes < 4096 || c.chunk_bytes % 16 || c.num_slots < 1 || c.num_slots > 64 ||
+    if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
+        c.host_engine > FLEX_ENGINE_SDMA || c.host_blocks < 1 || c.host_blocks > 65536 || c.pipeline_depth < 1 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -517,8 +595,12 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal, (uint32_t)cus};
-    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus};
+    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal, (uint32_t)cus, 0};
+    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
+    // host path kernels: a fixed, small number of workgroups striding over the
+    // step, so that PCIe-bound waves do not crowd the device path off the CUs
+    m->host_reduce_shape = {256, 1, 0, 0, (uint32_t)cus, c.host_blocks};
+    m->host_copy_shape = {256, 2, 0, 0, (uint32_t)cus, c.host_blocks};
 
     // Side streams at the default priority.
     CREATE_TRY(hipStreamCreateWithFlags(&m->s_d2h, hipStreamNonBlocking));
@@ -529,7 +611,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     if (nranks > 1) {
         for (uint32_t s = 0; s < c.num_slots; ++s) {
             void* p = nullptr;
-            CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes, hipHostMallocDefault));
+            CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes * (size_t)(nranks - 1), hipHostMallocDefault));
             m->pinned.push_back(p);
             hipEvent_t e = nullptr;
             CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -546,7 +628,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
         per_peer = std::min(per_peer, max_bytes_per_rank);
         per_peer = (per_peer + 255) / 256 * 256;
         m->scratch_stride = per_peer;
-        if (c.max_host_units > 0 && max_bytes_per_rank > 0)
+        if (c.host_engine == FLEX_ENGINE_SDMA && c.max_host_units > 0 && max_bytes_per_rank > 0)
             CREATE_TRY(hipMalloc((void**)&m->scratch, per_peer * (size_t)(nranks - 1)));
         m->ring.resize(kRingSize);
         for (auto& rec : m->ring) {
@@ -662,7 +744,7 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     if (comm->nranks > 1 && probe > 0)
         split = flex::partition(count, probe, bc.share_total, comm->cfg.split_align_elems,
                                 comm->cfg.min_split_bytes / es);
-    if (split < count && (count - split) * es <= comm->scratch_stride) {
+    if (split < count) {
         st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, probe, T);
         if (st) return st;
         res.path_bw[FLEX_PATH_HOST] = T[FLEX_PATH_HOST] > 0 ? (double)(count - split) * es / T[FLEX_PATH_HOST] : 0.0;

@@ -62,8 +62,9 @@ struct LaunchShape {
     uint32_t threads;       // workgroup size
     uint32_t unroll;        // 16-byte vectors per thread per input per tile
     uint32_t waves_per_cu;  // 0 = one workgroup per tile
-    uint32_t nontemporal;
+    uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device
+    uint32_t max_blocks;    // 0 = no limit; else the grid never exceeds this many workgroups
 };
 
 // Enqueue out[i] = sum over r (rank order) of in[r][i], i in [0, count), on

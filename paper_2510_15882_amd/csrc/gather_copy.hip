@@ -149,6 +149,11 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
         if (per_slice == 0) per_slice = 1;
         if (gx > per_slice) gx = per_slice;
     }
+    if (shape.max_blocks) {
+        uint64_t per_slice = shape.max_blocks / (uint32_t)n;
+        if (per_slice == 0) per_slice = 1;
+        if (gx > per_slice) gx = per_slice;
+    }
     if (gx == 0) gx = 1;
     if (gx > 0x7fffffffull) gx = 0x7fffffffull;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);

@@ -225,6 +225,7 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     // persistent grid's worth beyond the tiles
     uint64_t sgrid = scalar_blocks < resident * 8 ? scalar_blocks : resident * 8;
     if (grid < sgrid) grid = sgrid;
+    if (shape.max_blocks && grid > shape.max_blocks) grid = shape.max_blocks;
     if (grid == 0) grid = 1;
     if (grid > 0x7fffffffull) grid = 0x7fffffffull;
 

@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Configurations 0, 3 and 4 on one MI355X: message-size sweep with the
+two-stage balancer, the tensor-parallel prefill shape, and the small
+launch-bound message.  Prints one JSON line per case.
+
+    python -m paper_2510_15882_amd.sweep --config 3      # 1..1024 MiB per rank, AR and AG
+    python -m paper_2510_15882_amd.sweep --config 4      # 65536 x 5120 bf16 AllReduce, 50 calls
+    python -m paper_2510_15882_amd.sweep --config 0      # 1 MiB fp32 AllReduce: latency
+
+Per case: Stage 1 on the hardware (rates of both paths, bandwidth-proportional
+initial shares, Algorithm 1), then adaptive calls (Stage 2), then the same
+number of device-only calls interleaved block by block for an A/B comparison.
+"""
+import argparse
+import json
+import sys
+import time
+
+import torch
+
+from . import binding as fx
+from . import workloads as wl
+
+N = 8
+
+
+def median(v):
+    v = sorted(v)
+    n = len(v)
+    return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
+
+
+def mad(v):
+    m = median(v)
+    return median([abs(x - m) for x in v])
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Case:
+    def __init__(self, w, dev="cuda:0", cfg=None):
+        self.w = w
+        self.bufs = wl.make_rank_buffers(w, dev)
+        es = self.bufs[0].element_size()
+        self.is_ar = w.collective == "allreduce"
+        self.coll = fx.FLEX_ALLREDUCE if self.is_ar else fx.FLEX_ALLGATHER
+        self.out = torch.empty(w.count if self.is_ar else N * w.count, dtype=w.dtype, device=dev)
+        self.hbm_bytes = (N + 1) * w.count * es if self.is_ar else 2 * N * w.count * es
+        self.alg_bytes = w.count * es if self.is_ar else N * w.count * es
+        self.comm = fx.flex_comm_create(N, 0, w.count * es, cfg)
+        self.stream = torch.cuda.Stream()
+        torch.cuda.synchronize()
+
+    def call(self):
+        if self.is_ar:
+            fx.flex_allreduce_local(self.comm, self.bufs, self.out, stream=self.stream)
+        else:
+            fx.flex_allgather_local(self.comm, self.bufs, self.out, stream=self.stream)
+
+    def timed(self, n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        with torch.cuda.stream(self.stream):
+            for a, b in evs:
+                a.record(self.stream)
+                self.call()
+                b.record(self.stream)
+        self.stream.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+
+    def close(self):
+        torch.cuda.synchronize()
+        fx.flex_comm_destroy(self.comm)
+
+
+def run_case(w, windows=20, cfg=None):
+    c = Case(w, cfg=cfg)
+    bc = fx.flex_config_default().balancer
+    calls = windows * bc.window
+    with torch.cuda.stream(c.stream):
+        res = fx.flex_comm_tune(c.comm, c.coll, c.bufs, c.out, stream=c.stream)
+    trajectory = []
+    adaptive_ms, device_ms = [], []
+    for _ in range(windows):
+        fx.flex_set_split(c.comm, c.coll, fx.FLEX_SPLIT_ADAPTIVE)
+        adaptive_ms += c.timed(bc.window)
+        fx.flex_evaluator_drain(c.comm)
+        st = fx.flex_get_stats(c.comm, c.coll, w.count, w.dtype)
+        trajectory.append(int(st.balancer.shares[1]))
+        fx.flex_set_split(c.comm, c.coll, fx.FLEX_SPLIT_STATIC, 0)
+        device_ms += c.timed(bc.window)
+    st = fx.flex_get_stats(c.comm, c.coll, w.count, w.dtype)
+    a, d = median(adaptive_ms), median(device_ms)
+    out = {
+        "config": w.index, "case": w.name, "MiB_per_rank": w.bytes_per_rank / wl.MIB,
+        "path_rate_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
+        "initial_host_share_pct": res.initial_shares[1] / 100.0,
+        "stage1_host_share_pct": res.shares[1] / 100.0, "stage1_iterations": res.iterations,
+        "host_active_after_stage1": bool(res.active_mask & 2),
+        "stage2_windows": windows, "stage2_adjustments": int(st.balancer.adjustments),
+        "converged_host_share_pct": trajectory[-1] / 100.0, "host_share_trajectory_units": trajectory,
+        "adaptive_ms": a, "adaptive_hbm_GBs": c.hbm_bytes / a / 1e6, "adaptive_algbw_GBs": c.alg_bytes / a / 1e6,
+        "device_only_ms": d, "device_only_hbm_GBs": c.hbm_bytes / d / 1e6,
+        "gain_pct": 100.0 * (d / a - 1.0), "mad_ms": [mad(adaptive_ms), mad(device_ms)],
+        "combined_faster": bool(d - a > 3 * max(mad(adaptive_ms), mad(device_ms))),
+        "calls_each": calls,
+    }
+    c.close()
+    return out
+
+
+def run_prefill(calls=50):
+    w = wl.config(4)
+    c = Case(w)
+    with torch.cuda.stream(c.stream):
+        res = fx.flex_comm_tune(c.comm, c.coll, c.bufs, c.out, stream=c.stream)
+    out = {"config": 4, "case": w.name, "MiB_per_rank": w.bytes_per_rank / wl.MIB,
+           "path_rate_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
+           "initial_host_share_pct": res.initial_shares[1] / 100.0, "stage1_host_share_pct": res.shares[1] / 100.0,
+           "stage1_iterations": res.iterations}
+    for mode, name in ((fx.FLEX_SPLIT_ADAPTIVE, "adaptive"), (fx.FLEX_SPLIT_STATIC, "device_only")):
+        fx.flex_set_split(c.comm, c.coll, mode, 0)
+        c.timed(5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(c.stream):
+            for _ in range(calls):            # back to back on one stream, no host sync
+                c.call()
+        c.stream.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / calls
+        out[name + "_ms_per_call"] = ms
+        out[name + "_hbm_GBs"] = c.hbm_bytes / ms / 1e6
+        out[name + "_algbw_GBs"] = c.alg_bytes / ms / 1e6
+    fx.flex_evaluator_drain(c.comm)
+    st = fx.flex_get_stats(c.comm, c.coll, w.count, w.dtype)
+    out["host_share_pct_after"] = st.balancer.shares[1] / 100.0
+    out["blocking_reads"] = int(st.blocking_reads)
+    c.close()
+    return out
+
+
+def run_small():
+    w = wl.config(0)
+    c = Case(w)
+    c.timed(20)
+    single = c.timed(200)
+    # back-to-back launches amortise the launch gap
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(c.stream):
+        e0.record(c.stream)
+        for _ in range(1000):
+            c.call()
+        e1.record(c.stream)
+    c.stream.synchronize()
+    per = e0.elapsed_time(e1) / 1000
+    # cold: rotate over distinct buffer sets larger than the caches
+    sets = [(wl.make_rank_buffers(w, "cuda:0"), torch.empty_like(c.out)) for _ in range(64)]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(c.stream):
+        e0.record(c.stream)
+        for k in range(640):
+            bufs, out = sets[k % 64]
+            fx.flex_allreduce_local(c.comm, bufs, out, stream=c.stream)
+        e1.record(c.stream)
+    c.stream.synchronize()
+    cold = e0.elapsed_time(e1) / 640
+    out = {"config": 0, "case": w.name, "event_bracketed_single_call_us": median(single) * 1e3,
+           "back_to_back_us_per_call": per * 1e3, "back_to_back_hbm_GBs": c.hbm_bytes / per / 1e6,
+           "rotating_64_buffer_sets_us_per_call": cold * 1e3, "rotating_hbm_GBs": c.hbm_bytes / cold / 1e6,
+           "note": "9 MiB of traffic per call: launch-bound; the warm figure is served by L2 / Infinity Cache"}
+    c.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, required=True, choices=[0, 3, 4])
+    ap.add_argument("--windows", type=int, default=20)
+    ap.add_argument("--max-mib", type=int, default=1024)
+    args = ap.parse_args()
+    assert torch.cuda.is_available(), "needs the GPU"
+    fx.lib()
+    torch.cuda.set_device(0)
+    if args.config == 0:
+        print(json.dumps(run_small()), flush=True)
+    elif args.config == 4:
+        print(json.dumps(run_prefill()), flush=True)
+    else:
+        for w in wl.sweep_workloads():
+            if w.bytes_per_rank > args.max_mib * wl.MIB:
+                continue
+            log("case", w.name)
+            print(json.dumps(run_case(w, windows=args.windows)), flush=True)
+            torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main()

@@ -208,15 +208,20 @@ def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
 
 # ------------------------------------------------- split over both paths
 
+ENGINES = [fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
+
+
+@pytest.mark.parametrize("engine", ENGINES)
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype):
+def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype, engine):
     count = (1 << 20) + 3
     w = wl.config(0) if dtype == torch.float32 else wl.config(2)
     bufs = wl.make_rank_buffers(w, DEV, count=count)
     want = oracle_allreduce(bufs)
-    for chunk, slots in ((64 << 10, 2), (4 << 20, 2), (256 << 10, 3)):
+    for chunk, slots, depth in ((64 << 10, 2, 4), (4 << 20, 2, 1), (256 << 10, 3, 4), (4 << 20, 1, 8)):
         for rank in (0, 3, 7):
-            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk, num_slots=slots) as comm:
+            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk, num_slots=slots, host_engine=engine,
+                      pipeline_depth=depth, min_step_bytes=32 << 10) as comm:
                 for units in (0, 1, 500, 1200, 2200, 10000):
                     say("allreduce split", dtype, chunk, rank, units)
                     fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
@@ -228,14 +233,15 @@ def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype):
                     assert st.last_split == fx.flex_partition(count, units, 10000, 2048, (64 << 10) // out.element_size())
 
 
-def test_allgather_bits_do_not_depend_on_split_chunk_or_rank():
+@pytest.mark.parametrize("engine", ENGINES)
+def test_allgather_bits_do_not_depend_on_split_chunk_or_rank(engine):
     dtype = torch.bfloat16
     count = (1 << 19) + 5
     slices = [wl.random_bits(count, dtype, 40 + r, DEV) for r in range(8)]
     want = oracle_allgather(slices).tobytes()
     for chunk in (64 << 10, 4 << 20):
         for rank in (0, 5):
-            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk) as comm:
+            with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk, host_engine=engine) as comm:
                 for units in (0, 1, 500, 2200, 10000):
                     say("allgather split", chunk, rank, units)
                     fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
@@ -245,14 +251,15 @@ def test_allgather_bits_do_not_depend_on_split_chunk_or_rank():
                     assert wl.to_numpy_bits(out).tobytes() == want, (chunk, rank, units)
 
 
-def test_back_to_back_calls_on_one_stream_and_repeatability():
+@pytest.mark.parametrize("engine", ENGINES)
+def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
     # many split calls queued without host synchronisation, staging slots and
     # scratch reused every call: every output must carry the same bits
     count = (1 << 20) + 2048 + 1
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want = oracle_allreduce(bufs)
     stream = torch.cuda.Stream()
-    with Comm(chunk_bytes=128 << 10) as comm:
+    with Comm(chunk_bytes=128 << 10, host_engine=engine, min_step_bytes=16 << 10) as comm:
         fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 700)
         outs = [torch.zeros(count, dtype=torch.bfloat16, device=DEV) for _ in range(50)]
         torch.cuda.synchronize()
@@ -290,12 +297,13 @@ def test_config1_allgather_bf16_256MiB():
         assert wl.to_numpy_bits(out).tobytes() == oracle_allgather(slices).tobytes()
 
 
-def test_config2_allreduce_bf16_256MiB_split_sweep():
+@pytest.mark.parametrize("engine", ENGINES)
+def test_config2_allreduce_bf16_256MiB_split_sweep(engine):
     w = wl.config(2)
     say("generating", w.name)
     bufs = wl.make_rank_buffers(w, DEV)
     want = oracle_allreduce(bufs)
-    with Comm(max_bytes=w.bytes_per_rank) as comm:
+    with Comm(max_bytes=w.bytes_per_rank, host_engine=engine) as comm:
         for units in (0, 500, 1200, 2200):
             say("config2 units", units)
             fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
