@@ -162,7 +162,10 @@ def main():
                 res = fx.flex_comm_tune(comm, coll, bufs, out, stream=stream)
                 tune[name] = {"path_bw_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
                               "initial_shares": list(res.initial_shares)[:2], "shares": list(res.shares)[:2],
-                              "iterations": res.iterations, "active_mask": res.active_mask}
+                              "iterations": res.iterations, "active_mask": res.active_mask,
+                              "balanced_shares": list(res.balanced_shares)[:2],
+                              "balanced_split_ms": res.combined_s * 1e3, "device_alone_ms": res.device_alone_s * 1e3,
+                              "reverted_to_device_only": bool(res.reverted)}
                 log("tuned", name, tune[name])
                 fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
         elif args.mode == "device":

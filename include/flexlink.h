@@ -141,6 +141,13 @@ int flex_balancer_update(flex_balancer_t* b, const double* path_time_s, uint32_t
 /* End Stage 1 now (no-op in Stage 2): later updates are Stage-2 samples. */
 int flex_balancer_finish_tuning(flex_balancer_t* b);
 
+/* Give every auxiliary path's share back to the primary path, deactivate them
+ * and end Stage 1: the state Algorithm 1 itself ends in when "only NVLink
+ * remains".  Used when the split, however balanced, is no faster than the
+ * primary path alone (paper, Section "Two-Stage Load Balancing Strategy": the
+ * system then reverts to the primary-only baseline). */
+int flex_balancer_revert_to_primary(flex_balancer_t* b);
+
 /* Copy the balancer's state to *out (host pointer). */
 int flex_balancer_get(const flex_balancer_t* b, flex_balancer_state_t* out);
 
@@ -201,6 +208,9 @@ typedef struct flex_config {
     uint32_t pipeline_depth;     /* a host part shorter than pipeline_depth * chunk_bytes per peer is still
                                     cut into up to this many steps so that the two stages overlap (default 4) */
     uint32_t min_step_bytes;     /* ... but no step is shorter than this per peer (default 256 KiB) */
+    uint32_t tune_accept_check;  /* 1 (default): flex_comm_tune keeps the tuned split only if it finishes
+                                    sooner than the device path alone, else reverts to device-only */
+    uint32_t reserved;
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 
@@ -227,6 +237,11 @@ typedef struct flex_tune_result {
     uint32_t active_mask;
     uint32_t iterations;                    /* Algorithm 1 iterations measured */
     double path_time_s[FLEX_MAX_PATHS];     /* last measured per-path times */
+    uint32_t balanced_shares[FLEX_MAX_PATHS]; /* shares Algorithm 1 ended with, before the acceptance check */
+    double device_alone_s;                  /* whole message on the device path alone (median) */
+    double combined_s;                      /* slowest path's time at balanced_shares (median); 0 if not measured */
+    uint32_t reverted;                      /* 1 = the acceptance check reverted to device-only */
+    uint32_t reserved;
 } flex_tune_result_t;
 
 /* Fill *cfg (host pointer) with defaults. */
@@ -308,7 +323,11 @@ int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units);
  * Coarse-Grained Tuning").  Blocking.  Runs collective `coll` on the given
  * buffers repeatedly: first to measure each path's rate (device path alone;
  * host path at probe_units), then Algorithm 1 with MeasurePathTimings = median
- * of tune_reps calls, until the balancer leaves Stage 1.  The resulting
+ * of tune_reps calls, until the balancer leaves Stage 1.  Then, unless
+ * tune_accept_check is 0 or the host path was already drained, the balanced
+ * split is timed once more against the device path alone and reverted to
+ * device-only if it is not faster (the two paths share the GPU's memory
+ * system, so a balanced split can be slower than no split).  The resulting
  * balancer is stored for the message's size class (replacing an older one).
  * Arguments as for the collective itself; `out` is overwritten with the
  * collective's (correct) result.  result may be NULL.

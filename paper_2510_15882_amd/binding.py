@@ -58,6 +58,7 @@ class Config(_Struct):
                 ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
                 ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("pipeline_depth", u32), ("min_step_bytes", u32),
+                ("tune_accept_check", u32), ("reserved", u32),
                 ("balancer", BalancerCfg)]
 
 
@@ -71,7 +72,8 @@ class Stats(_Struct):
 class TuneResult(_Struct):
     _fields_ = [("path_bw", f64 * FLEX_MAX_PATHS), ("initial_shares", u32 * FLEX_MAX_PATHS),
                 ("shares", u32 * FLEX_MAX_PATHS), ("active_mask", u32), ("iterations", u32),
-                ("path_time_s", f64 * FLEX_MAX_PATHS)]
+                ("path_time_s", f64 * FLEX_MAX_PATHS), ("balanced_shares", u32 * FLEX_MAX_PATHS),
+                ("device_alone_s", f64), ("combined_s", f64), ("reverted", u32), ("reserved", u32)]
 
 
 class FlexError(RuntimeError):
@@ -104,6 +106,7 @@ def lib():
         "flex_balancer_init_shares": [pvp, ci, P(u32), P(BalancerCfg)],
         "flex_balancer_update": [vp, P(f64), P(u32)],
         "flex_balancer_finish_tuning": [vp],
+        "flex_balancer_revert_to_primary": [vp],
         "flex_balancer_get": [vp, P(BalancerState)],
         "flex_balancer_destroy": [vp],
         "flex_partition": [u64, u32, u32, u32, u64, P(u64)],
@@ -179,6 +182,10 @@ def flex_balancer_update(b, path_time_s):
 
 def flex_balancer_finish_tuning(b):
     _check(lib().flex_balancer_finish_tuning(b))
+
+
+def flex_balancer_revert_to_primary(b):
+    _check(lib().flex_balancer_revert_to_primary(b))
 
 
 def flex_balancer_get(b):

@@ -163,6 +163,15 @@ void Balancer::finish_tuning() {
     }
 }
 
+void Balancer::revert_to_primary() {
+    for (int p = 1; p < npaths; ++p) {
+        shares[0] += shares[p];
+        shares[p] = 0;
+    }
+    active_mask = 1u;
+    finish_tuning();
+}
+
 void Balancer::get(flex_balancer_state_t* o) const {
     o->npaths = (uint32_t)npaths;
     o->stage = stage;
@@ -246,6 +255,12 @@ int flex_balancer_update(flex_balancer_t* b, const double* path_time_s, uint32_t
 int flex_balancer_finish_tuning(flex_balancer_t* b) {
     if (!b) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_balancer_finish_tuning: b is NULL");
     b->impl.finish_tuning();
+    return FLEX_OK;
+}
+
+int flex_balancer_revert_to_primary(flex_balancer_t* b) {
+    if (!b) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_balancer_revert_to_primary: b is NULL");
+    b->impl.revert_to_primary();
     return FLEX_OK;
 }
 

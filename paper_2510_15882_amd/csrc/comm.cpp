@@ -539,9 +539,10 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->reduce_nontemporal = 1;
     cfg->copy_nontemporal = 3;
     cfg->host_engine = FLEX_ENGINE_KERNEL;
-    cfg->host_blocks = 64;
+    cfg->host_blocks = 16;
     cfg->pipeline_depth = 4;
     cfg->min_step_bytes = 256u << 10;
+    cfg->tune_accept_check = 1;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -765,6 +766,37 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
         if (!sc.bal.update(T))
             return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: unusable path timings (%g s, %g s)", T[0], T[1]);
     }
+    for (int p = 0; p < 2; ++p) res.balanced_shares[p] = sc.bal.shares[p];
+    res.device_alone_s = t_dev_alone;
+
+    // Acceptance check: the balanced split must beat the device path alone.
+    if (comm->cfg.tune_accept_check && (sc.bal.active_mask & (1u << FLEX_PATH_HOST))) {
+        uint32_t units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+        double Tc[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, Tc);
+        if (st) return st;
+        res.combined_s = std::max(Tc[FLEX_PATH_DEVICE], Tc[FLEX_PATH_HOST]);
+        // device path alone again, right next to it
+        cs.static_units = 0;
+        std::vector<double> again;
+        for (uint32_t k = 0; k < comm->cfg.tune_reps + 1; ++k) {
+            HIP_TRY(hipEventRecord(comm->t0, stream));
+            st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
+            if (st) return st;
+            HIP_TRY(hipEventRecord(comm->t1, stream));
+            HIP_TRY(hipEventSynchronize(comm->t1));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, comm->t0, comm->t1));
+            if (k > 0) again.push_back(ms * 1e-3);
+        }
+        std::sort(again.begin(), again.end());
+        res.device_alone_s = again[again.size() / 2];
+        if (!(res.combined_s < res.device_alone_s)) {
+            sc.bal.revert_to_primary();
+            res.reverted = 1;
+        }
+    }
+
     // leave `out` holding a result computed after the last share change
     cs.static_units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
     st = comm->collective(coll, rank_bufs, out, count, dtype, stream);

@@ -47,6 +47,7 @@ struct Balancer {
     bool init_from_shares(int np, const uint32_t* s, const flex_balancer_cfg_t& c);
     bool update(const double* T);  // false: bad times, state unchanged
     void finish_tuning();
+    void revert_to_primary();
     void get(flex_balancer_state_t* o) const;
 
    private:

@@ -96,7 +96,9 @@ def run_case(w, windows=20, cfg=None):
         "config": w.index, "case": w.name, "MiB_per_rank": w.bytes_per_rank / wl.MIB,
         "path_rate_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
         "initial_host_share_pct": res.initial_shares[1] / 100.0,
-        "stage1_host_share_pct": res.shares[1] / 100.0, "stage1_iterations": res.iterations,
+        "balanced_host_share_pct": res.balanced_shares[1] / 100.0, "stage1_iterations": res.iterations,
+        "balanced_split_ms": res.combined_s * 1e3, "device_alone_ms": res.device_alone_s * 1e3,
+        "reverted_to_device_only": bool(res.reverted), "stage1_host_share_pct": res.shares[1] / 100.0,
         "host_active_after_stage1": bool(res.active_mask & 2),
         "stage2_windows": windows, "stage2_adjustments": int(st.balancer.adjustments),
         "converged_host_share_pct": trajectory[-1] / 100.0, "host_share_trajectory_units": trajectory,
@@ -117,8 +119,10 @@ def run_prefill(calls=50):
         res = fx.flex_comm_tune(c.comm, c.coll, c.bufs, c.out, stream=c.stream)
     out = {"config": 4, "case": w.name, "MiB_per_rank": w.bytes_per_rank / wl.MIB,
            "path_rate_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
-           "initial_host_share_pct": res.initial_shares[1] / 100.0, "stage1_host_share_pct": res.shares[1] / 100.0,
-           "stage1_iterations": res.iterations}
+           "initial_host_share_pct": res.initial_shares[1] / 100.0,
+           "balanced_host_share_pct": res.balanced_shares[1] / 100.0, "balanced_split_ms": res.combined_s * 1e3,
+           "device_alone_ms": res.device_alone_s * 1e3, "reverted_to_device_only": bool(res.reverted),
+           "stage1_host_share_pct": res.shares[1] / 100.0, "stage1_iterations": res.iterations}
     for mode, name in ((fx.FLEX_SPLIT_ADAPTIVE, "adaptive"), (fx.FLEX_SPLIT_STATIC, "device_only")):
         fx.flex_set_split(c.comm, c.coll, mode, 0)
         c.timed(5)

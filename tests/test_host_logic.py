@@ -34,7 +34,8 @@ def test_struct_layout_defaults_come_through():
     assert c.chunk_bytes == 4 << 20 and c.num_slots == 2 and c.max_host_units == 2500
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 1 and c.copy_nontemporal == 3
-    assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 64, 4, 256 << 10)
+    assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 16, 4, 256 << 10)
+    assert c.tune_accept_check == 1
     b = c.balancer
     assert (b.share_total, b.initial_step, b.stability_required, b.max_tune_iters, b.window,
             b.runtime_step) == (10000, 64, 3, 100, 10, 4)
@@ -191,3 +192,13 @@ def test_library_partition_rejects_bad_input():
         fx.flex_partition(100, 10001)
     with pytest.raises(fx.FlexError):
         fx.flex_partition(100, 1, align_elems=0)
+
+
+def test_library_revert_to_primary():
+    b = fx.flex_balancer_init_shares([9000, 600, 400], cfg())
+    fx.flex_balancer_revert_to_primary(b)
+    s = fx.flex_balancer_get(b)
+    assert list(s.shares)[:3] == [10000, 0, 0] and s.active_mask == 1 and s.stage == fx.FLEX_STAGE_RUNTIME
+    for _ in range(25):      # drained paths never come back
+        assert fx.flex_balancer_update(b, [5.0, 0.0, 0.0]) == [10000, 0, 0]
+    fx.flex_balancer_destroy(b)
