@@ -8,6 +8,13 @@ the C ABI with the two-path split chosen by the tuned, adaptive balancer
 (partition -> device path + host-staged path -> join -> evaluate/rebalance).
 Inputs are resident in HBM before the timed region starts.
 
+Successive steps rotate over --buffer-sets independent sets of input and output
+buffers (default 3, about 8 GiB in all), so that every byte a step touches was
+last touched several GiB of traffic earlier: the 256 MB Infinity Cache cannot
+keep an output buffer resident from one call to the next and the HBM traffic
+equals the algorithmic bytes.  The same-buffers-every-call figure (what
+nccl-tests style loops measure) is reported under extras.warm_same_buffers.
+
 Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
 timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
 dominant kernel (the N-way reduce) against the 8 TB/s HBM3E peak from per-launch
@@ -25,7 +32,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PCIE_PEAK_GBS = 64.0
 METRIC = "AllReduce/AllGather local-share GB/s at 256MB (8 sim ranks); % HBM peak"
+N = 8
 
 
 def log(*a):
@@ -51,7 +60,7 @@ def read_traffic_note():
     return None
 
 
-def cpu_baseline(oc, wl, ar_host, ag_host, ar_bytes, ag_bytes, passes=3):
+def cpu_baseline(oc, ar_host, ag_host, ar_bytes, ag_bytes, passes=3):
     threads = oc.get_threads()
     oc.allreduce(ar_host)          # warm pass (page faults, thread pool)
     oc.allgather(ag_host)
@@ -65,7 +74,8 @@ def cpu_baseline(oc, wl, ar_host, ag_host, ar_bytes, ag_bytes, passes=3):
     return {"value": (ar_bytes + ag_bytes) / best / 1e9, "unit": "GB/s", "cores": threads,
             "kind": "oracle", "seconds_per_step": best,
             "sample": "the full step (configuration 2 AllReduce + configuration 1 AllGather), same bytes as "
-                      "the GPU run; best of %d passes after one warm pass, %d OpenMP threads" % (passes, threads)}
+                      "buffer set 0 of the GPU run; best of %d passes after one warm pass, %d OpenMP threads"
+                      % (passes, threads)}
 
 
 def main():
@@ -75,11 +85,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--mode", default="adaptive",
                     help="adaptive (tuned balancer) | device (host share 0) | static:UNITS (of 10000)")
+    ap.add_argument("--buffer-sets", type=int, default=3, help="independent buffer sets the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only launch a plain copy of known size (1-rank AllGather of 1 GiB, 10 launches): the "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--no-extras", action="store_true", help="skip the untimed device-only / static-split legs")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed warm / static-split legs")
     ap.add_argument("--reduce-threads", type=int, default=0)
     ap.add_argument("--reduce-unroll", type=int, default=0)
     ap.add_argument("--reduce-waves", type=int, default=0)
@@ -88,6 +99,8 @@ def main():
     ap.add_argument("--copy-waves", type=int, default=0)
     ap.add_argument("--reduce-nt", type=int, default=-1)
     ap.add_argument("--copy-nt", type=int, default=-1)
+    ap.add_argument("--host-engine", type=int, default=-1)
+    ap.add_argument("--host-blocks", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is the single-GPU local share; it runs on exactly one GPU "
@@ -114,58 +127,74 @@ def main():
         print(json.dumps({"calibration": "gather_copy_kernel, 1 rank, 10 launches",
                           "read_bytes_per_launch": 2 * n, "write_bytes_per_launch": 2 * n}))
         return
+
     w_ar, w_ag = wl.config(2), wl.config(1)
-    N = 8
-    log("generating inputs on the GPU ...")
-    ar_bufs = wl.make_rank_buffers(w_ar, dev)
-    ag_slices = wl.make_rank_buffers(w_ag, dev)
-    ar_out = torch.empty(w_ar.count, dtype=w_ar.dtype, device=dev)
-    ag_out = torch.empty(N * w_ag.count, dtype=w_ag.dtype, device=dev)
+    nsets = max(1, args.buffer_sets)
+    log("generating %d buffer set(s) on the GPU ..." % nsets)
+    sets = []
+    for k in range(nsets):
+        ar_bufs = wl.make_rank_buffers(w_ar, dev)        # every set holds the same seeded values
+        ag_slices = wl.make_rank_buffers(w_ag, dev)
+        sets.append((ar_bufs, torch.empty(w_ar.count, dtype=w_ar.dtype, device=dev),
+                     ag_slices, torch.empty(N * w_ag.count, dtype=w_ag.dtype, device=dev)))
     ar_bytes = (N + 1) * w_ar.bytes_per_rank
     ag_bytes = 2 * N * w_ag.bytes_per_rank
 
     cfg = fx.flex_config_default()
-    cfg.reduce_threads, cfg.reduce_unroll, cfg.reduce_waves_per_cu = args.reduce_threads, args.reduce_unroll, args.reduce_waves
-    cfg.copy_threads, cfg.copy_unroll, cfg.copy_waves_per_cu = args.copy_threads, args.copy_unroll, args.copy_waves
-    if args.reduce_nt >= 0:
-        cfg.reduce_nontemporal = args.reduce_nt
-    if args.copy_nt >= 0:
-        cfg.copy_nontemporal = args.copy_nt
+    effective = {}
+    for key, val in (("reduce_threads", args.reduce_threads), ("reduce_unroll", args.reduce_unroll),
+                     ("reduce_waves_per_cu", args.reduce_waves), ("copy_threads", args.copy_threads),
+                     ("copy_unroll", args.copy_unroll), ("copy_waves_per_cu", args.copy_waves),
+                     ("host_blocks", args.host_blocks)):
+        if val:
+            setattr(cfg, key, val)
+    for key, val in (("reduce_nontemporal", args.reduce_nt), ("copy_nontemporal", args.copy_nt),
+                     ("host_engine", args.host_engine)):
+        if val >= 0:
+            setattr(cfg, key, val)
+    for key in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu", "reduce_nontemporal", "copy_threads",
+                "copy_unroll", "copy_waves_per_cu", "copy_nontemporal", "host_engine", "host_blocks",
+                "chunk_bytes", "num_slots", "pipeline_depth"):
+        effective[key] = getattr(cfg, key)
     comm = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
 
-    def ar():
-        fx.flex_allreduce_local(comm, ar_bufs, ar_out, stream=stream)
+    def ar(k=0):
+        s = sets[k % nsets]
+        fx.flex_allreduce_local(comm, s[0], s[1], stream=stream)
 
-    def ag():
-        fx.flex_allgather_local(comm, ag_slices, ag_out, stream=stream)
+    def ag(k=0):
+        s = sets[k % nsets]
+        fx.flex_allgather_local(comm, s[2], s[3], stream=stream)
 
-    def timed_calls(fn, n):
-        """Median per-call milliseconds of n calls, HIP events on the launch stream."""
+    def timed_calls(fn, n, rotate):
+        """Per-call milliseconds of n calls, HIP events on the launch stream."""
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
         with torch.cuda.stream(stream):
-            for a, b in evs:
+            for k, (a, b) in enumerate(evs):
                 a.record(stream)
-                fn()
+                fn(k if rotate else 0)
                 b.record(stream)
         stream.synchronize()
         return [a.elapsed_time(b) for a, b in evs]
 
-    extras = {}
+    def stats(coll, w):
+        return fx.flex_get_stats(comm, coll, w.count, w.dtype)
+
     tune = {}
     with torch.cuda.stream(stream):
         # ---- untimed: Stage 1 of the balancer, or a fixed split ----------
         if args.mode == "adaptive":
-            for coll, bufs, out, name in ((fx.FLEX_ALLREDUCE, ar_bufs, ar_out, "allreduce"),
-                                          (fx.FLEX_ALLGATHER, ag_slices, ag_out, "allgather")):
+            for coll, bufs, out, name in ((fx.FLEX_ALLREDUCE, sets[0][0], sets[0][1], "allreduce"),
+                                          (fx.FLEX_ALLGATHER, sets[0][2], sets[0][3], "allgather")):
                 res = fx.flex_comm_tune(comm, coll, bufs, out, stream=stream)
-                tune[name] = {"path_bw_GBs": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
-                              "initial_shares": list(res.initial_shares)[:2], "shares": list(res.shares)[:2],
-                              "iterations": res.iterations, "active_mask": res.active_mask,
+                tune[name] = {"path_rate_GBs_of_message": [res.path_bw[0] / 1e9, res.path_bw[1] / 1e9],
+                              "initial_shares": list(res.initial_shares)[:2],
                               "balanced_shares": list(res.balanced_shares)[:2],
                               "balanced_split_ms": res.combined_s * 1e3, "device_alone_ms": res.device_alone_s * 1e3,
-                              "reverted_to_device_only": bool(res.reverted)}
+                              "reverted_to_device_only": bool(res.reverted),
+                              "shares": list(res.shares)[:2], "iterations": res.iterations}
                 log("tuned", name, tune[name])
                 fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
         elif args.mode == "device":
@@ -177,12 +206,12 @@ def main():
         else:
             sys.exit("unknown --mode")
 
-        for _ in range(args.warmup):
-            ar()
-            ag()
+        for k in range(args.warmup):
+            ar(k)
+            ag(k)
     stream.synchronize()
     fx.flex_evaluator_drain(comm)
-    s_ar0 = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
+    s_ar0 = stats(fx.FLEX_ALLREDUCE, w_ar)
 
     # ---- timed region: exactly --steps steps --------------------------------
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -191,15 +220,15 @@ def main():
     with torch.cuda.stream(stream):
         for k in range(args.steps):
             ev[k][0].record(stream)
-            ar()
+            ar(k)
             ev[k][1].record(stream)
-            ag()
+            ag(k)
             ev[k][2].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     fx.flex_evaluator_drain(comm)
-    s_ar1 = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
-    s_ag1 = fx.flex_get_stats(comm, fx.FLEX_ALLGATHER, w_ag.count, w_ag.dtype)
+    s_ar1 = stats(fx.FLEX_ALLREDUCE, w_ar)
+    s_ag1 = stats(fx.FLEX_ALLGATHER, w_ag)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = (ar_bytes + ag_bytes) / (ms_per_step * 1e-3) / 1e9
@@ -217,13 +246,16 @@ def main():
         how = "Evaluator events fork->device-path-done, mean of %d split calls" % split_samples
     else:
         kern_ms = sum(ar_ms) / len(ar_ms)
-        how = "HIP events around each launch on the launch stream, mean of %d" % len(ar_ms)
+        how = "HIP events around each launch on the launch stream, mean of %d launches" % len(ar_ms)
     bytes_per_elem = (N + 1) * 2
     achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "reduce_n_kernel<8, bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note(),
                 "launch_ms": kern_ms, "elements_per_launch": int(dev_elems), "bytes_per_element": bytes_per_elem,
-                "timing": how}
+                "algorithmic_bytes_per_launch": int(bytes_per_elem * dev_elems), "timing": how}
+
+    def host_units(st):
+        return int(st.balancer.shares[1]) if args.mode == "adaptive" else int(st.static_host_units)
 
     result = {
         "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -231,51 +263,62 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[2] AllReduce bf16 8 ranks x 256 MiB (fp32 accumulate) + configs[1] "
                                "AllGather bf16 8 x 32 MiB -> 256 MiB, one call each per step",
-                   "mode": args.mode, "nranks": N, "algorithmic_bytes_per_step": ar_bytes + ag_bytes,
-                   "launch (0 = library default)": {k: getattr(cfg, k) for k in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu",
-                                                            "copy_threads", "copy_unroll", "copy_waves_per_cu",
-                                                            "reduce_nontemporal", "copy_nontemporal")}},
+                   "mode": args.mode, "nranks": N, "buffer_sets": nsets,
+                   "algorithmic_bytes_per_step": ar_bytes + ag_bytes, "library": effective},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": roofline,
         "allreduce": {"ms_median": median(ar_ms), "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,
                       "algbw_GBs": w_ar.bytes_per_rank / (median(ar_ms) * 1e-3) / 1e9,
-                      "host_units": int(s_ar1.balancer.shares[1]) if args.mode == "adaptive" else s_ar1.static_host_units,
-                      "split_calls_timed": int(split_samples)},
+                      "host_units": host_units(s_ar1), "split_calls_timed": int(split_samples)},
         "allgather": {"ms_median": median(ag_ms), "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
                       "algbw_GBs": N * w_ag.bytes_per_rank / (median(ag_ms) * 1e-3) / 1e9,
-                      "host_units": int(s_ag1.balancer.shares[1]) if args.mode == "adaptive" else s_ag1.static_host_units},
+                      "host_units": host_units(s_ag1)},
     }
     if tune:
         result["tune"] = tune
 
-    # ---- untimed extras: device-only and the static split sweep -------------
+    # ---- untimed extras ------------------------------------------------------
     if not args.no_extras:
+        extras = {}
         for coll in (fx.FLEX_ALLREDUCE, fx.FLEX_ALLGATHER):
             fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_STATIC, 0)
-        d_ar = median(timed_calls(ar, 50))
-        d_ag = median(timed_calls(ag, 50))
-        extras["device_only"] = {"allreduce_ms": d_ar, "allreduce_hbm_GBs": ar_bytes / d_ar / 1e6,
-                                 "allgather_ms": d_ag, "allgather_hbm_GBs": ag_bytes / d_ag / 1e6}
+        for name, rotate in (("device_only_rotating_buffers", True), ("warm_same_buffers", False)):
+            d_ar = median(timed_calls(ar, 60, rotate))
+            d_ag = median(timed_calls(ag, 60, rotate))
+            extras[name] = {"allreduce_ms": d_ar, "allreduce_hbm_GBs": ar_bytes / d_ar / 1e6,
+                            "allgather_ms": d_ag, "allgather_hbm_GBs": ag_bytes / d_ag / 1e6}
+        extras["warm_same_buffers"]["note"] = ("the 256 MiB output stays resident in the 256 MB Infinity Cache "
+                                               "between calls: HBM sees fewer bytes than the algorithm moves")
+        # configuration 2's static split sweep: device-only vs 5 / 12 / 22 % through pinned host memory
         sweep = {}
-        for units in (100, 500, 1200, 2200):
+        for units in (0, 100, 500, 1200, 2200):
             fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
-            ms = median(timed_calls(ar, 10))
+            timed_calls(ar, 2, True)
             fx.flex_evaluator_drain(comm)
-            st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, w_ar.count, w_ar.dtype)
-            host_elems = st.last_count - st.last_split
-            pcie_bytes = (N - 1) * host_elems * 2          # each direction
-            sweep[str(units)] = {"allreduce_ms": ms, "hbm_GBs": ar_bytes / ms / 1e6,
-                                 "device_path_ms": st.last_time_s[0] * 1e3, "host_path_ms": st.last_time_s[1] * 1e3,
-                                 "pcie_GBs_per_direction": pcie_bytes / st.last_time_s[1] / 1e9 if st.last_time_s[1] > 0 else None}
+            b = stats(fx.FLEX_ALLREDUCE, w_ar)
+            ms = median(timed_calls(ar, 10, True))
+            fx.flex_evaluator_drain(comm)
+            a = stats(fx.FLEX_ALLREDUCE, w_ar)
+            row = {"allreduce_ms": ms, "hbm_GBs": ar_bytes / ms / 1e6, "algbw_GBs": w_ar.bytes_per_rank / ms / 1e6}
+            n = a.samples - b.samples
+            if n > 0:
+                t_dev = (a.mean_time_s[0] * a.samples - b.mean_time_s[0] * b.samples) / n
+                t_host = (a.mean_time_s[1] * a.samples - b.mean_time_s[1] * b.samples) / n
+                host_elems = a.last_count - a.last_split
+                pcie = (N - 1) * host_elems * 2 / t_host / 1e9
+                row.update({"host_share_pct": 100.0 * host_elems / a.last_count, "device_path_ms": t_dev * 1e3,
+                            "host_path_ms": t_host * 1e3, "pcie_GBs_per_direction": pcie,
+                            "pcie_frac_of_64GBs": pcie / PCIE_PEAK_GBS})
+            sweep[str(units)] = row
         extras["allreduce_static_split"] = sweep
         result["extras"] = extras
 
     if not args.no_cpu_baseline:
         from oracle import collectives as oc
         log("timing the CPU oracle ...")
-        ar_host = [wl.to_numpy_bits(b) for b in ar_bufs]
-        ag_host = [wl.to_numpy_bits(b) for b in ag_slices]
-        result["cpu_baseline"] = cpu_baseline(oc, wl, ar_host, ag_host, ar_bytes, ag_bytes)
+        ar_host = [wl.to_numpy_bits(b) for b in sets[0][0]]
+        ag_host = [wl.to_numpy_bits(b) for b in sets[0][2]]
+        result["cpu_baseline"] = cpu_baseline(oc, ar_host, ag_host, ar_bytes, ag_bytes)
 
     torch.cuda.synchronize()
     fx.flex_comm_destroy(comm)

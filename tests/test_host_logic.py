@@ -33,7 +33,7 @@ def test_struct_layout_defaults_come_through():
     c = fx.flex_config_default()
     assert c.chunk_bytes == 4 << 20 and c.num_slots == 2 and c.max_host_units == 2500
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
-    assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 1 and c.copy_nontemporal == 3
+    assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
     assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 16, 4, 256 << 10)
     assert c.tune_accept_check == 1
     b = c.balancer
