@@ -335,6 +335,15 @@ int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units);
 int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
                    int dtype, void* hip_stream, flex_tune_result_t* result);
 
+/* Install explicit shares for the size class of a message of `count` elements of
+ * `dtype` (for example shares saved from an earlier flex_comm_tune): the class
+ * gets a balancer in Stage 2 holding them, marked as tuned.
+ *   shares  host array of 2 units {device, host} summing to share_total;
+ *           a path given 0 units is inactive.
+ * Errors: INVALID_ARG (null, unknown collective, sum != share_total, host share
+ * above max_host_units), UNSUPPORTED (dtype). */
+int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares);
+
 /* Evaluator: read back the timing records of finished calls without blocking
  * (also done at the start of every collective call). */
 int flex_evaluator_poll(flex_comm_t* comm);

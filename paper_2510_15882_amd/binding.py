@@ -117,6 +117,7 @@ def lib():
         "flex_allgather_local": [vp, pvp, vp, sz, ci, vp],
         "flex_set_split": [vp, ci, ci, u32],
         "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
+        "flex_comm_set_shares": [vp, ci, sz, ci, P(u32)],
         "flex_evaluator_poll": [vp],
         "flex_evaluator_drain": [vp],
         "flex_get_stats": [vp, ci, sz, ci, P(Stats)],
@@ -279,6 +280,11 @@ def flex_comm_tune(comm, coll, rank_bufs, out, count=None, stream=None):
     _check(lib().flex_comm_tune(comm, coll, _pointer_array(rank_bufs), out.data_ptr(), count,
                                 dtype_code(out.dtype), _stream_handle(stream), ctypes.byref(res)))
     return res
+
+
+def flex_comm_set_shares(comm, coll, count, dtype, shares):
+    arr = (u32 * 2)(*shares)
+    _check(lib().flex_comm_set_shares(comm, coll, count, dtype_code(dtype), arr))
 
 
 def flex_evaluator_poll(comm):

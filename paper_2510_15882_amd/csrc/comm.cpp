@@ -820,6 +820,27 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     return FLEX_OK;
 }
 
+int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares) {
+    if (!comm || !shares) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: NULL argument");
+    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: unknown collective %d", coll);
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_set_shares: unknown dtype %d", dtype);
+    if (shares[FLEX_PATH_HOST] > comm->cfg.max_host_units)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: host share %u exceeds max_host_units %u",
+                          shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+    SizeClass sc;
+    sc.tuned = true;
+    if (!sc.bal.init_from_shares(2, shares, comm->cfg.balancer))
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: shares must sum to share_total");
+    sc.bal.finish_tuning();
+    auto& slot = comm->coll[coll].classes[size_class_of(count * es)];
+    const uint64_t gen = slot.generation + 1;
+    slot = sc;
+    slot.generation = gen;
+    return FLEX_OK;
+}
+
 int flex_evaluator_poll(flex_comm_t* comm) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_evaluator_poll: comm is NULL");
     return comm->poll(false);

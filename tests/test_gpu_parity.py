@@ -412,6 +412,56 @@ def test_tune_then_adaptive_stays_exact_and_balanced():
         assert_same_bits(out_ar[:count // 2], oracle_allreduce(half), "borrowed class")
 
 
+@pytest.mark.parametrize("engine", ENGINES)
+def test_stage2_runs_on_hardware(engine):
+    # explicit shares keep the host path active, so the Evaluator feeds real
+    # per-path times into Stage 2 while calls keep coming
+    count = 32 * wl.MIB        # 64 MiB per rank
+    bufs = wl.make_rank_buffers(wl.config(1), DEV, count=count)
+    want = oracle_allreduce(bufs)
+    with Comm(max_bytes=count * 2, host_engine=engine) as comm:
+        out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+        with pytest.raises(fx.FlexError):
+            fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9000, 999])
+        fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9900, 100])
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
+        trajectory = [100]
+        for k in range(80):
+            fx.flex_allreduce_local(comm, bufs, out)
+            if k % 10 == 9:
+                torch.cuda.synchronize()
+                assert_same_bits(out, want, "adaptive call %d" % k)
+                fx.flex_evaluator_drain(comm)
+                st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+                trajectory.append(int(st.balancer.shares[1]))
+                assert sum(st.balancer.shares) == 10000 and st.balancer.stage == fx.FLEX_STAGE_RUNTIME
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+        say("stats", st.as_dict(), trajectory)
+        assert st.samples == 80 and st.split_calls == 80
+        assert 1 <= st.balancer.adjustments <= 8                # the paths are far from balance at 1 %
+        # every window moves at most one fixed step of 4 units
+        assert all(abs(b - a) in (0, 4) for a, b in zip(trajectory, trajectory[1:]))
+        # samples measured before a share change are not fed into the next window:
+        # a move needs a full window of 10 samples taken at the current shares
+        assert st.balancer.adjustments <= 80 // 10
+
+
+def test_tune_acceptance_check_never_leaves_a_slower_split():
+    count = 64 * wl.MIB        # 128 MiB per rank
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    with Comm(max_bytes=count * 2) as comm:
+        out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+        res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
+        say("tune", res.as_dict())
+        if res.reverted:
+            assert list(res.shares)[:2] == [10000, 0] and res.active_mask == 1
+            assert res.combined_s >= res.device_alone_s > 0 and res.balanced_shares[1] > 0
+        elif res.active_mask & 2:
+            assert res.combined_s < res.device_alone_s
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), "after tune")
+
+
 # ------------------------------------------------------------ error handling
 
 def test_invalid_arguments_are_rejected_without_enqueueing():
