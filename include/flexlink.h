@@ -59,9 +59,9 @@ enum flex_status {
     FLEX_ERR_STATE = 5        /* call not valid in the object's current state */
 };
 
-enum flex_dtype { FLEX_F32 = 0, FLEX_BF16 = 1 };
+enum flex_dtype { FLEX_F32 = 0, FLEX_BF16 = 1, FLEX_F16 = 2 };
 enum flex_op { FLEX_SUM = 0 };
-enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1 };
+enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1, FLEX_REDUCESCATTER = 2 };
 enum flex_path { FLEX_PATH_DEVICE = 0, FLEX_PATH_HOST = 1 };
 enum flex_split_mode { FLEX_SPLIT_STATIC = 0, FLEX_SPLIT_ADAPTIVE = 1 };
 enum flex_balancer_stage { FLEX_STAGE_TUNING = 1, FLEX_STAGE_RUNTIME = 2 };
@@ -275,12 +275,13 @@ int flex_comm_destroy(flex_comm_t* comm);
  *              during the call.
  *   out        device pointer to `count` elements.
  *   count      elements per rank (0 is allowed: nothing is enqueued).
- *   dtype      FLEX_F32 or FLEX_BF16.   op: FLEX_SUM.
+ *   dtype      FLEX_F32, FLEX_BF16 or FLEX_F16.   op: FLEX_SUM.
  *   hip_stream the caller's hipStream_t (NULL = the default stream).
  * Result, for every i:  out[i] = round(((b0[i] + b1[i]) + b2[i]) + ... ) with
  * the additions done in IEEE binary32, round-to-nearest-even, strictly in rank
  * order starting from rank 0's value, and one final rounding to dtype
- * (bfloat16: round-to-nearest-even; a NaN result is some quiet NaN).  The bits
+ * (bfloat16 and binary16: round-to-nearest-even, subnormals kept; a NaN result
+ * is some NaN).  The bits
  * of out do not depend on the split, the chunk size, `rank` or the launch
  * shape.  Elements [0, split) are reduced by the device path on hip_stream;
  * peers' elements [split, count) travel through the pinned transit buffers on
@@ -293,6 +294,22 @@ int flex_comm_destroy(flex_comm_t* comm);
  * count * size > max_bytes_per_rank), UNSUPPORTED (dtype, op), HIP. */
 int flex_allreduce_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t count,
                          int dtype, int op, void* hip_stream);
+
+/* ReduceScatter(sum), local share: the strict one-rank view of the first half of
+ * the paper's ring AllReduce (Evaluation, "End-to-End Performance": N-1
+ * reduce-scatter steps, after which rank r owns the fully reduced slice r).
+ *   rank_bufs   host array of nranks device pointers; rank_bufs[r] holds rank r's
+ *               nranks * recv_count contiguous elements (slice s at offset
+ *               s * recv_count).
+ *   out         device pointer to recv_count elements.
+ * Result: out[j] = sum over r, in rank order, of rank_bufs[r][rank*recv_count + j],
+ * with exactly the arithmetic, split, engines and error behaviour of
+ * flex_allreduce_local (it is that reduction applied to the local rank's slice;
+ * HBM traffic (nranks+1) * recv_count elements).  nranks * recv_count * size
+ * must not exceed max_bytes_per_rank.  Followed by flex_allgather_local over the
+ * nranks reduced slices it gives the AllReduce a real rank performs. */
+int flex_reducescatter_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t recv_count,
+                             int dtype, int op, void* hip_stream);
 
 /* AllGather, local share (paper: same section; N-1 ring steps that place every
  * rank's slice at its rank offset).

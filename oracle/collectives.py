@@ -22,6 +22,12 @@ def lib():
         L.oracle_allreduce_f32.restype = None
         L.oracle_allreduce_bf16.argtypes = [pp, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
         L.oracle_allreduce_bf16.restype = None
+        L.oracle_allreduce_f16.argtypes = [pp, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
+        L.oracle_allreduce_f16.restype = None
+        L.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+        L.oracle_f16_to_f32.restype = ctypes.c_float
+        L.oracle_f32_bits_to_f16.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.oracle_f32_bits_to_f16.restype = None
         L.oracle_allgather.argtypes = [pp, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
         L.oracle_allgather.restype = None
         L.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -57,8 +63,8 @@ def _check_inputs(bufs):
 def allreduce(bufs):
     """Rank-ordered sum of the rank buffers.
 
-    bufs: list of N 1-D arrays, all float32, or all uint16 holding bfloat16
-    bit patterns.  Returns a new array of the same dtype and length.
+    bufs: list of N 1-D arrays, all float32, all float16, or all uint16 holding
+    bfloat16 bit patterns.  Returns a new array of the same dtype and length.
     """
     _check_inputs(bufs)
     out = np.empty_like(bufs[0])
@@ -67,9 +73,22 @@ def allreduce(bufs):
         lib().oracle_allreduce_f32(ptrs, len(bufs), bufs[0].size, out.ctypes.data)
     elif bufs[0].dtype == np.uint16:
         lib().oracle_allreduce_bf16(ptrs, len(bufs), bufs[0].size, out.ctypes.data)
+    elif bufs[0].dtype == np.float16:
+        lib().oracle_allreduce_f16(ptrs, len(bufs), bufs[0].size, out.ctypes.data)
     else:
-        raise ValueError("dtype must be float32 or uint16 (bfloat16 bits)")
+        raise ValueError("dtype must be float32, float16 or uint16 (bfloat16 bits)")
     return out
+
+
+def reducescatter(bufs, rank):
+    """Rank `rank`'s slice of the rank-ordered sum: every buffer holds N slices
+    of equal length; the result is the sum over ranks of slice number `rank`."""
+    _check_inputs(bufs)
+    n = len(bufs)
+    if bufs[0].size % n:
+        raise ValueError("buffer length must be a multiple of the number of ranks")
+    rc = bufs[0].size // n
+    return allreduce([np.ascontiguousarray(b[rank * rc:(rank + 1) * rc]) for b in bufs])
 
 
 def allgather(slices):
@@ -94,6 +113,18 @@ def f32_bits_to_bf16(bits):
     bits = np.ascontiguousarray(bits, dtype=np.uint32)
     out = np.empty(bits.shape, dtype=np.uint16)
     lib().oracle_f32_bits_to_bf16(bits.ctypes.data, bits.size, out.ctypes.data)
+    return out
+
+
+def f16_to_f32(h: int) -> float:
+    return float(lib().oracle_f16_to_f32(int(h)))
+
+
+def f32_bits_to_f16(bits):
+    """Round an array of binary32 bit patterns (uint32) to binary16 bits."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint32)
+    out = np.empty(bits.shape, dtype=np.uint16)
+    lib().oracle_f32_bits_to_f16(bits.ctypes.data, bits.size, out.ctypes.data)
     return out
 
 

@@ -56,6 +56,66 @@ static uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+/* IEEE binary16 -> binary32 (exact).  1 sign, 5 exponent (bias 15), 10 mantissa
+ * bits.  Normal numbers re-bias the exponent (127 - 15 = 112) and left-align
+ * the mantissa; subnormals are m * 2^-24; exponent 31 is infinity or NaN. */
+static float f16_bits_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1fu;
+    uint32_t m = h & 0x3ffu;
+    uint32_t u;
+    if (e == 0) {
+        float mag = (float)m * 0x1p-24f;            /* exact: m < 1024 */
+        memcpy(&u, &mag, sizeof u);
+        u |= sign;
+    } else if (e == 31) {
+        u = sign | 0x7f800000u | (m << 13);
+    } else {
+        u = sign | ((e + 112u) << 23) | (m << 13);
+    }
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* binary32 -> IEEE binary16, round to nearest, ties to even.  Magnitudes of
+ * 2^16 and above (and anything that rounds up to 2^16) become infinity; below
+ * the smallest normal 2^-14 the result is a multiple of 2^-24 (subnormal),
+ * obtained by shifting the 24-bit significand right and rounding what falls
+ * off.  NaN stays NaN (quiet bit set, upper payload kept). */
+static uint16_t f32_to_f16_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t mag = u & 0x7fffffffu;
+    uint32_t e32 = mag >> 23;
+    uint32_t mant = mag & 0x7fffffu;
+    if (mag > 0x7f800000u)
+        return (uint16_t)(sign | 0x7e00u | (mant >> 13));
+    if (mag >= 0x47800000u)                         /* |f| >= 2^16, or infinity */
+        return (uint16_t)(sign | 0x7c00u);
+    if (e32 >= 113) {                               /* normal binary16 range */
+        uint32_t h = ((e32 - 112u) << 10) | (mant >> 13);
+        uint32_t rem = mant & 0x1fffu;
+        if (rem > 0x1000u || (rem == 0x1000u && (h & 1u)))
+            h += 1;                                 /* may carry up to 0x7c00 = infinity */
+        return (uint16_t)(sign | h);
+    }
+    /* subnormal or zero result: value = sig * 2^(e32 - 150), quantum 2^-24 */
+    uint32_t shift = 126u - e32;
+    if (e32 == 0 || shift > 25)
+        return sign;                                /* below 2^-26: rounds to zero */
+    uint32_t sig = mant | 0x800000u;
+    uint32_t h = sig >> shift;
+    uint32_t rem = sig & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (h & 1u)))
+        h += 1;                                     /* may carry up to 0x0400 = smallest normal */
+    return (uint16_t)(sign | h);
+}
+
 /* AllReduce(sum), binary32 elements.
  * b: n pointers to `count` floats each (rank r's contribution is b[r]).
  * out[i] = ((b[0][i] + b[1][i]) + b[2][i]) + ... + b[n-1][i]. */
@@ -85,6 +145,20 @@ void oracle_allreduce_bf16(const uint16_t *const *b, int n, size_t count, uint16
     }
 }
 
+/* AllReduce(sum), IEEE binary16 elements given as raw 16-bit patterns.
+ * Accumulate in binary32 in rank order, round once at the end. */
+void oracle_allreduce_f16(const uint16_t *const *b, int n, size_t count, uint16_t *out)
+{
+    long long i;
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < (long long)count; ++i) {
+        float acc = f16_bits_to_f32(b[0][i]);
+        for (int r = 1; r < n; ++r)
+            acc = acc + f16_bits_to_f32(b[r][i]);
+        out[i] = f32_to_f16_bits(acc);
+    }
+}
+
 /* AllGather: out is the concatenation, in rank order, of n slices of
  * slice_bytes bytes each.  Bytes are moved untouched. */
 void oracle_allgather(const void *const *in, int n, size_t slice_bytes, void *out)
@@ -111,6 +185,17 @@ void oracle_f32_bits_to_bf16(const uint32_t *bits, size_t n, uint16_t *out)
         float f;
         memcpy(&f, &bits[i], sizeof f);
         out[i] = f32_to_bf16_bits(f);
+    }
+}
+
+float oracle_f16_to_f32(uint16_t h) { return f16_bits_to_f32(h); }
+
+void oracle_f32_bits_to_f16(const uint32_t *bits, size_t n, uint16_t *out)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float f;
+        memcpy(&f, &bits[i], sizeof f);
+        out[i] = f32_to_f16_bits(f);
     }
 }
 

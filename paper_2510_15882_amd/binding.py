@@ -15,9 +15,9 @@ FLEX_MAX_RANKS = 8
 FLEX_MAX_PATHS = 4
 
 FLEX_OK, FLEX_ERR_INVALID_ARG, FLEX_ERR_UNSUPPORTED, FLEX_ERR_HIP, FLEX_ERR_NOMEM, FLEX_ERR_STATE = range(6)
-FLEX_F32, FLEX_BF16 = 0, 1
+FLEX_F32, FLEX_BF16, FLEX_F16 = 0, 1, 2
 FLEX_SUM = 0
-FLEX_ALLREDUCE, FLEX_ALLGATHER = 0, 1
+FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER = 0, 1, 2
 FLEX_PATH_DEVICE, FLEX_PATH_HOST = 0, 1
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
@@ -115,6 +115,7 @@ def lib():
         "flex_comm_destroy": [vp],
         "flex_allreduce_local": [vp, pvp, vp, sz, ci, ci, vp],
         "flex_allgather_local": [vp, pvp, vp, sz, ci, vp],
+        "flex_reducescatter_local": [vp, pvp, vp, sz, ci, ci, vp],
         "flex_set_split": [vp, ci, ci, u32],
         "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
         "flex_comm_set_shares": [vp, ci, sz, ci, P(u32)],
@@ -218,6 +219,8 @@ def dtype_code(dtype):
         return FLEX_F32
     if dtype == torch.bfloat16:
         return FLEX_BF16
+    if dtype == torch.float16:
+        return FLEX_F16
     raise ValueError("unsupported dtype %r" % (dtype,))
 
 
@@ -260,6 +263,14 @@ def flex_allreduce_local(comm, rank_bufs, out, count=None, op=FLEX_SUM, stream=N
     count = rank_bufs[0].numel() if count is None else count
     _check(lib().flex_allreduce_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
                                       dtype_code(out.dtype), op, _stream_handle(stream)))
+
+
+def flex_reducescatter_local(comm, rank_bufs, out, recv_count=None, op=FLEX_SUM, stream=None):
+    """rank_bufs: list of nranks device tensors of nranks * recv_count elements."""
+    _check_tensors(rank_bufs, out)
+    recv_count = rank_bufs[0].numel() // len(rank_bufs) if recv_count is None else recv_count
+    _check(lib().flex_reducescatter_local(comm, _pointer_array(rank_bufs), out.data_ptr(), recv_count,
+                                          dtype_code(out.dtype), op, _stream_handle(stream)))
 
 
 def flex_allgather_local(comm, rank_slices, out, slice_count=None, stream=None):

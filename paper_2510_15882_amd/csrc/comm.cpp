@@ -107,7 +107,7 @@ struct flex_comm {
     uint64_t blocking_reads = 0;
     hipEvent_t t0 = nullptr, t1 = nullptr;  // device-only timing in flex_comm_tune
 
-    CollState coll[2];
+    CollState coll[3];  // indexed by flex_coll
 
     // ---- host-staged path --------------------------------------------------
     // What the consumer stage does with a step once it sits in the pinned slot.
@@ -317,10 +317,15 @@ struct flex_comm {
         return FLEX_OK;
     }
 
-    int allreduce(const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream);
+    // AllReduce, or (c == FLEX_REDUCESCATTER) the same reduction over the
+    // local rank's slice of every input
+    int reduce(int c, const char* who, const void* const* bufs, void* out, size_t count, int dtype,
+               hipStream_t stream);
+    int reducescatter(const void* const* bufs, void* out, size_t recv_count, int dtype, hipStream_t stream);
     int allgather(const void* const* slices, void* out, size_t count, int dtype, hipStream_t stream);
     int collective(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream) {
-        return c == FLEX_ALLREDUCE ? allreduce(bufs, out, count, dtype, stream)
+        if (c == FLEX_REDUCESCATTER) return reducescatter(bufs, out, count, dtype, stream);
+        return c == FLEX_ALLREDUCE ? reduce(c, "flex_allreduce_local", bufs, out, count, dtype, stream)
                                    : allgather(bufs, out, count, dtype, stream);
     }
     int validate(const char* who, const void* const* bufs, const void* out, size_t count, int dtype);
@@ -349,11 +354,30 @@ int flex_comm::validate(const char* who, const void* const* bufs, const void* ou
     return check_device();
 }
 
-int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int dtype,
-                         hipStream_t stream) {
-    int st = validate("flex_allreduce_local", bufs, out, count, dtype);
+int flex_comm::reducescatter(const void* const* bufs, void* out, size_t recv_count, int dtype,
+                             hipStream_t stream) {
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_reducescatter_local: unknown dtype %d", dtype);
+    if (!bufs) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_reducescatter_local: rank pointer array is NULL");
+    if (recv_count > max_bytes / es / (size_t)nranks)
+        return flex::fail(FLEX_ERR_INVALID_ARG,
+                          "flex_reducescatter_local: %d x %zu elements exceed max_bytes_per_rank %zu", nranks,
+                          recv_count, max_bytes);
+    // rank r's slice of every contribution starts rank * recv_count elements in
+    const void* slice[FLEX_MAX_RANKS];
+    for (int r = 0; r < nranks; ++r) {
+        if (recv_count > 0 && !bufs[r])
+            return flex::fail(FLEX_ERR_INVALID_ARG, "flex_reducescatter_local: rank %d pointer is NULL", r);
+        slice[r] = (const char*)bufs[r] + (size_t)rank * recv_count * es;
+    }
+    return reduce(FLEX_REDUCESCATTER, "flex_reducescatter_local", slice, out, recv_count, dtype, stream);
+}
+
+int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out, size_t count, int dtype,
+                      hipStream_t stream) {
+    int st = validate(who, bufs, out, count, dtype);
     if (st) return st;
-    CollState& cs = coll[FLEX_ALLREDUCE];
+    CollState& cs = coll[c];
     ++cs.calls;
     if (count == 0) return FLEX_OK;
     st = poll(false);
@@ -362,7 +386,7 @@ int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int d
     const size_t es = flex::dtype_size(dtype);
     bool adaptive;
     SizeClass* sc;
-    const uint32_t units = units_for_call(FLEX_ALLREDUCE, count * es, &adaptive, &sc);
+    const uint32_t units = units_for_call(c, count * es, &adaptive, &sc);
     const uint64_t split = flex::partition(count, units, cfg.balancer.share_total, cfg.split_align_elems,
                                            cfg.min_split_bytes / es);
     const size_t host_count = count - split;
@@ -375,15 +399,14 @@ int flex_comm::allreduce(const void* const* bufs, void* out, size_t count, int d
     }
     if (cfg.host_engine == FLEX_ENGINE_SDMA && host_count * es > scratch_stride)
         return flex::fail(FLEX_ERR_INVALID_ARG,
-                          "flex_allreduce_local: host part of %zu bytes exceeds the scratch sized by "
-                          "max_host_units (%zu bytes per peer)",
-                          host_count * es, scratch_stride);
+                          "%s: host part of %zu bytes exceeds the scratch sized by max_host_units (%zu bytes per peer)",
+                          who, host_count * es, scratch_stride);
 
     ++cs.split_calls;
     TimingRecord* rec;
     st = acquire_record(&rec);
     if (st) return st;
-    rec->coll = FLEX_ALLREDUCE;
+    rec->coll = c;
     rec->size_class = size_class_of(count * es);
     rec->adaptive = adaptive;
     rec->generation = sc ? sc->generation : 0;
@@ -669,7 +692,15 @@ int flex_allreduce_local(flex_comm_t* comm, const void* const* rank_bufs, void* 
                          int dtype, int op, void* hip_stream) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_allreduce_local: comm is NULL");
     if (op != FLEX_SUM) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_allreduce_local: unknown op %d", op);
-    return comm->allreduce(rank_bufs, out, count, dtype, (hipStream_t)hip_stream);
+    return comm->reduce(FLEX_ALLREDUCE, "flex_allreduce_local", rank_bufs, out, count, dtype,
+                        (hipStream_t)hip_stream);
+}
+
+int flex_reducescatter_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t recv_count,
+                             int dtype, int op, void* hip_stream) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_reducescatter_local: comm is NULL");
+    if (op != FLEX_SUM) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_reducescatter_local: unknown op %d", op);
+    return comm->reducescatter(rank_bufs, out, recv_count, dtype, (hipStream_t)hip_stream);
 }
 
 int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
@@ -680,7 +711,7 @@ int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void
 
 int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: comm is NULL");
-    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown collective %d", coll);
     if (mode != FLEX_SPLIT_STATIC && mode != FLEX_SPLIT_ADAPTIVE)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown mode %d", mode);
@@ -695,7 +726,7 @@ int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
 int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
                    int dtype, void* hip_stream, flex_tune_result_t* result) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: comm is NULL");
-    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: unknown collective %d", coll);
     int st = comm->validate("flex_comm_tune", rank_bufs, out, count, dtype);
     if (st) return st;
@@ -822,7 +853,7 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
 
 int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares) {
     if (!comm || !shares) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: NULL argument");
-    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: unknown collective %d", coll);
     const size_t es = flex::dtype_size(dtype);
     if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_set_shares: unknown dtype %d", dtype);
@@ -853,7 +884,7 @@ int flex_evaluator_drain(flex_comm_t* comm) {
 
 int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out) {
     if (!comm || !out) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: NULL argument");
-    if (coll != FLEX_ALLREDUCE && coll != FLEX_ALLGATHER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: unknown collective %d", coll);
     const size_t es = flex::dtype_size(dtype);
     if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_get_stats: unknown dtype %d", dtype);

@@ -79,7 +79,9 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
 int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t* bytes, int n,
                        const LaunchShape& shape, void* stream);
 
-inline size_t dtype_size(int dtype) { return dtype == FLEX_F32 ? 4 : dtype == FLEX_BF16 ? 2 : 0; }
+inline size_t dtype_size(int dtype) {
+    return dtype == FLEX_F32 ? 4 : (dtype == FLEX_BF16 || dtype == FLEX_F16) ? 2 : 0;
+}
 
 }  // namespace flex
 

@@ -53,21 +53,47 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return ((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded;
 }
 
+// binary16 <-> binary32 through the hardware converters: the widening is exact,
+// the narrowing rounds to nearest even (the default rounding mode) and keeps
+// binary16 subnormals; a NaN stays a NaN.
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// Element types (values of flex_dtype).
+constexpr int kF32 = FLEX_F32, kBF16 = FLEX_BF16, kF16 = FLEX_F16;
+
+template <int DT>
+__device__ __forceinline__ float widen_low(uint32_t w) {
+    return DT == kBF16 ? bf16_low_to_f32(w) : f16_bits_to_f32(w & 0xffffu);
+}
+template <int DT>
+__device__ __forceinline__ float widen_high(uint32_t w) {
+    return DT == kBF16 ? bf16_high_to_f32(w) : f16_bits_to_f32(w >> 16);
+}
+template <int DT>
+__device__ __forceinline__ uint32_t narrow(float f) {
+    return DT == kBF16 ? f32_to_bf16_bits(f) : f32_to_f16_bits(f);
+}
+
 // One 16-byte vector from each of N inputs -> one 16-byte result.
-template <int N, bool BF16>
+template <int N, int DT>
 __device__ __forceinline__ u32x4 reduce_vectors(const u32x4 (&v)[N]) {
     u32x4 o;
-    if (BF16) {
+    if (DT != kF32) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            float lo = bf16_low_to_f32(v[0][w]);
-            float hi = bf16_high_to_f32(v[0][w]);
+            float lo = widen_low<DT>(v[0][w]);
+            float hi = widen_high<DT>(v[0][w]);
 #pragma unroll
             for (int r = 1; r < N; ++r) {
-                lo = lo + bf16_low_to_f32(v[r][w]);
-                hi = hi + bf16_high_to_f32(v[r][w]);
+                lo = lo + widen_low<DT>(v[r][w]);
+                hi = hi + widen_high<DT>(v[r][w]);
             }
-            o[w] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+            o[w] = narrow<DT>(lo) | (narrow<DT>(hi) << 16);
         }
     } else {
 #pragma unroll
@@ -81,14 +107,13 @@ __device__ __forceinline__ u32x4 reduce_vectors(const u32x4 (&v)[N]) {
     return o;
 }
 
-template <int N, bool BF16>
+template <int N, int DT>
 __device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t i) {
-    if (BF16) {
-        float acc = __uint_as_float((uint32_t)((const uint16_t*)a.in[0])[i] << 16);
+    if (DT != kF32) {
+        float acc = widen_low<DT>(((const uint16_t*)a.in[0])[i]);
 #pragma unroll
-        for (int r = 1; r < N; ++r)
-            acc = acc + __uint_as_float((uint32_t)((const uint16_t*)a.in[r])[i] << 16);
-        ((uint16_t*)a.out)[i] = (uint16_t)f32_to_bf16_bits(acc);
+        for (int r = 1; r < N; ++r) acc = acc + widen_low<DT>(((const uint16_t*)a.in[r])[i]);
+        ((uint16_t*)a.out)[i] = (uint16_t)narrow<DT>(acc);
     } else {
         float acc = ((const float*)a.in[0])[i];
 #pragma unroll
@@ -97,9 +122,9 @@ __device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t
     }
 }
 
-template <int N, bool BF16, int UNROLL, bool LDNT, bool STNT>
+template <int N, int DT, int UNROLL, bool LDNT, bool STNT>
 __global__ void reduce_n_kernel(ReduceArgs a) {
-    constexpr uint32_t kElemSize = BF16 ? 2 : 4;
+    constexpr uint32_t kElemSize = DT == kF32 ? 4 : 2;
     constexpr uint32_t kVecElems = 16 / kElemSize;
     const uint32_t tid = threadIdx.x;
     const uint32_t nthreads = blockDim.x;
@@ -123,7 +148,7 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
                     v[u][r] = load16<LDNT>(in[r] + first + (uint64_t)u * nthreads + tid);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
-                store16<STNT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, BF16>(v[u]));
+                store16<STNT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, DT>(v[u]));
         } else {
             // ragged last tile
             for (int u = 0; u < UNROLL; ++u) {
@@ -132,7 +157,7 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
                     u32x4 v[N];
 #pragma unroll
                     for (int r = 0; r < N; ++r) v[r] = load16<LDNT>(in[r] + idx);
-                    store16<STNT>(out + idx, reduce_vectors<N, BF16>(v));
+                    store16<STNT>(out + idx, reduce_vectors<N, DT>(v));
                 }
             }
         }
@@ -144,43 +169,43 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     for (uint64_t k = (uint64_t)blockIdx.x * nthreads + tid; k < nscalar;
          k += (uint64_t)gridDim.x * nthreads) {
         const uint64_t i = k < a.head ? k : body_end + (k - a.head);
-        reduce_one_element<N, BF16>(a, i);
+        reduce_one_element<N, DT>(a, i);
     }
 }
 
-template <int N, bool BF16, int UNROLL>
+template <int N, int DT, int UNROLL>
 int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
     switch (nt & 3u) {
-        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, false, true>), dim3(grid), dim3(threads), 0, stream, a); break;
-        default: hipLaunchKernelGGL((reduce_n_kernel<N, BF16, UNROLL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, false, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+        default: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
     }
     return (int)hipGetLastError();
 }
 
-template <int N, bool BF16>
+template <int N, int DT>
 int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
              hipStream_t stream) {
     switch (unroll) {
-        case 1: return launch_one<N, BF16, 1>(a, grid, threads, nt, stream);
-        case 2: return launch_one<N, BF16, 2>(a, grid, threads, nt, stream);
-        default: return launch_one<N, BF16, 4>(a, grid, threads, nt, stream);
+        case 1: return launch_one<N, DT, 1>(a, grid, threads, nt, stream);
+        case 2: return launch_one<N, DT, 2>(a, grid, threads, nt, stream);
+        default: return launch_one<N, DT, 4>(a, grid, threads, nt, stream);
     }
 }
 
-template <bool BF16>
+template <int DT>
 int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
                  hipStream_t stream) {
     switch (n) {
-        case 1: return launch_n<1, BF16>(a, grid, threads, unroll, nt, stream);
-        case 2: return launch_n<2, BF16>(a, grid, threads, unroll, nt, stream);
-        case 3: return launch_n<3, BF16>(a, grid, threads, unroll, nt, stream);
-        case 4: return launch_n<4, BF16>(a, grid, threads, unroll, nt, stream);
-        case 5: return launch_n<5, BF16>(a, grid, threads, unroll, nt, stream);
-        case 6: return launch_n<6, BF16>(a, grid, threads, unroll, nt, stream);
-        case 7: return launch_n<7, BF16>(a, grid, threads, unroll, nt, stream);
-        default: return launch_n<8, BF16>(a, grid, threads, unroll, nt, stream);
+        case 1: return launch_n<1, DT>(a, grid, threads, unroll, nt, stream);
+        case 2: return launch_n<2, DT>(a, grid, threads, unroll, nt, stream);
+        case 3: return launch_n<3, DT>(a, grid, threads, unroll, nt, stream);
+        case 4: return launch_n<4, DT>(a, grid, threads, unroll, nt, stream);
+        case 5: return launch_n<5, DT>(a, grid, threads, unroll, nt, stream);
+        case 6: return launch_n<6, DT>(a, grid, threads, unroll, nt, stream);
+        case 7: return launch_n<7, DT>(a, grid, threads, unroll, nt, stream);
+        default: return launch_n<8, DT>(a, grid, threads, unroll, nt, stream);
     }
 }
 
@@ -231,8 +256,10 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
 
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)
-        return launch_dtype<true>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
-    return launch_dtype<false>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+        return launch_dtype<kBF16>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+    if (dtype == FLEX_F16)
+        return launch_dtype<kF16>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+    return launch_dtype<kF32>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
 }
 
 }  // namespace flex

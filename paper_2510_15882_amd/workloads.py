@@ -121,6 +121,13 @@ def random_bits(count: int, dtype: torch.dtype, seed: int, device="cpu", finite_
             exp_all_ones = (bits & 0x7F80) == 0x7F80
             bits = torch.where(exp_all_ones, bits & ~0x4000, bits)
         return bits.view(torch.bfloat16)
+    if dtype == torch.float16:
+        bits = torch.randint(-(1 << 15), 1 << 15, (count,), dtype=torch.int64,
+                             generator=g, device=device).to(torch.int16)
+        if finite_only:
+            exp_all_ones = (bits & 0x7C00) == 0x7C00
+            bits = torch.where(exp_all_ones, bits & ~0x4000, bits)
+        return bits.view(torch.float16)
     raise ValueError(dtype)
 
 
@@ -132,4 +139,6 @@ def to_numpy_bits(t: torch.Tensor):
         return t.numpy()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view("uint16")
+    if t.dtype == torch.float16:
+        return t.numpy()
     raise ValueError(t.dtype)

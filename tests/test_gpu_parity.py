@@ -47,10 +47,12 @@ class Comm:
 
 def assert_same_bits(got: torch.Tensor, want_bits: np.ndarray, what=""):
     got_bits = wl.to_numpy_bits(got)
-    if got_bits.dtype == np.float32:
+    if got.dtype == torch.float32:
         g, w = got_bits.view(np.uint32), want_bits.view(np.uint32)
-        nan = np.isnan(want_bits)
-        got_nan = np.isnan(got_bits)
+        nan, got_nan = np.isnan(want_bits), np.isnan(got_bits)
+    elif got.dtype == torch.float16:
+        g, w = got_bits.view(np.uint16), want_bits.view(np.uint16)
+        nan, got_nan = np.isnan(want_bits), np.isnan(got_bits)
     else:
         g, w = got_bits, want_bits
         nan = ((w & 0x7F80) == 0x7F80) & ((w & 0x7F) != 0)
@@ -77,7 +79,7 @@ COUNTS = [0, 1, 7, 8, 9, 2047, 2048, 2049, 65536, (1 << 20) + 3]
 
 # ------------------------------------------------------------ device path
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("nranks", [1, 2, 3, 8])
 def test_allreduce_device_path_all_counts(dtype, nranks):
     with Comm(nranks=nranks) as comm:
@@ -93,7 +95,7 @@ def test_allreduce_device_path_all_counts(dtype, nranks):
             assert torch.all(out[count:] == 7.0), "wrote past the end"
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_allreduce_raw_bit_patterns_and_specials(dtype):
     count = 300007
     with Comm() as comm:
@@ -103,7 +105,7 @@ def test_allreduce_raw_bit_patterns_and_specials(dtype):
         torch.cuda.synchronize()
         assert_same_bits(out, oracle_allreduce(bufs), "raw bits")
         # denormal inputs and sums stay denormal (no flushing)
-        tiny = torch.full((4099,), 1e-40, dtype=torch.float32, device=DEV).to(dtype)
+        tiny = torch.full((4099,), 1e-40 if dtype != torch.float16 else 6e-8, dtype=torch.float32, device=DEV).to(dtype)
         bufs = [tiny * (r + 1) for r in range(8)]
         out = torch.empty(4099, dtype=dtype, device=DEV)
         fx.flex_allreduce_local(comm, bufs, out)
@@ -111,6 +113,12 @@ def test_allreduce_raw_bit_patterns_and_specials(dtype):
         want = oracle_allreduce(bufs)
         assert want.view(np.uint32 if dtype == torch.float32 else np.uint16)[0] != 0
         assert_same_bits(out, want, "denormals")
+        if dtype == torch.float16:
+            # sums that land on the overflow threshold and in the subnormal range
+            edge = torch.tensor([65504.0, 8190.0, 2.0 ** -24, 2.0 ** -14, 0.33], device=DEV).repeat(800).to(dtype)
+            fx.flex_allreduce_local(comm, [edge] * 8, out[:4000], count=4000)
+            torch.cuda.synchronize()
+            assert_same_bits(out[:4000], oracle_allreduce([edge] * 8), "f16 edges")
         # signed zero: starts from rank 0's value
         neg0 = torch.full((1000,), -0.0, dtype=dtype, device=DEV)
         fx.flex_allreduce_local(comm, [neg0] * 8, out[:1000], count=1000)
@@ -204,6 +212,41 @@ def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
         torch.cuda.synchronize()
         assert_same_bits(out, want_ar, "allreduce")
         assert wl.to_numpy_bits(out2).tobytes() == want_ag.tobytes()
+
+
+# ---------------------------------------------------------- ReduceScatter
+
+@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+def test_reducescatter_is_the_rank_slice_and_composes_to_allreduce(dtype, engine):
+    n = 8
+    for rc in (0, 1, 2049, 65536 + 7, (1 << 18) + 2048):
+        total = n * rc
+        w = wl.config(0) if dtype == torch.float32 else wl.config(2)
+        bufs = [b.to(dtype) for b in wl.make_rank_buffers(w, DEV, count=total)]
+        if dtype == torch.float16:
+            bufs = [b * 50 for b in bufs]
+        host = [wl.to_numpy_bits(b) for b in bufs]
+        want_full = oc.allreduce(host) if total else None
+        reduced = []
+        for rank in range(n):
+            with Comm(rank=rank, max_host_units=10000, host_engine=engine) as comm:
+                units = (0, 900, 10000)[rank % 3]
+                fx.flex_set_split(comm, fx.FLEX_REDUCESCATTER, fx.FLEX_SPLIT_STATIC, units)
+                out = torch.full((rc + 4,), 3.0, dtype=dtype, device=DEV)
+                fx.flex_reducescatter_local(comm, bufs, out, recv_count=rc)
+                torch.cuda.synchronize()
+                if rc:
+                    assert_same_bits(out[:rc], oc.reducescatter(host, rank), "rank %d rc %d" % (rank, rc))
+                assert torch.all(out[rc:] == 3.0)
+                reduced.append(out[:rc].clone())
+        if rc:
+            # all-gather of the reduced slices = the AllReduce result
+            with Comm(max_host_units=10000) as comm:
+                full = torch.zeros(total, dtype=dtype, device=DEV)
+                fx.flex_allgather_local(comm, reduced, full)
+                torch.cuda.synchronize()
+                assert_same_bits(full, want_full, "reduce-scatter + all-gather, rc %d" % rc)
 
 
 # ------------------------------------------------- split over both paths
@@ -492,7 +535,7 @@ def test_invalid_arguments_are_rejected_without_enqueueing():
         with pytest.raises(fx.FlexError):
             fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 2501)
         with pytest.raises(fx.FlexError):
-            fx.flex_set_split(comm, 2, fx.FLEX_SPLIT_STATIC, 0)
+            fx.flex_set_split(comm, 3, fx.FLEX_SPLIT_STATIC, 0)
         torch.cuda.synchronize()
         assert out.abs().sum() == 0          # nothing ran
         # count 0 is fine and does nothing

@@ -289,3 +289,91 @@ def test_every_rank_contributes_once():
     bufs = [np.arange(500, dtype=np.float32) + 1000 * r for r in range(n)]
     want = np.arange(500, dtype=np.int64) * n + 1000 * sum(range(n))
     assert np.array_equal(oc.allreduce(bufs).astype(np.int64), want)
+
+
+# ------------------------------------------------------------- binary16
+
+def test_f16_widening_is_exact_for_all_patterns():
+    allbits = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    want = allbits.view(np.float16).astype(np.float32)
+    got = np.array([oc.f16_to_f32(int(h)) for h in allbits[::7]], dtype=np.float32)
+    w = want[::7]
+    fin = ~np.isnan(w)
+    assert np.array_equal(got[fin].view(np.uint32), w[fin].view(np.uint32))
+    assert np.all(np.isnan(got[~fin]))
+
+
+def test_f16_rounding_matches_library_rne():
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x0FFF, 0x1000, 0x1001, 0x1FFF, 0x2000, 0x3000, 0x7FFF, 0x8000, 0xFFFF],
+                    dtype=np.uint32)
+    bits = (hi[:, None] | lows[None, :]).reshape(-1).astype(np.uint32)
+    # dense sweeps where the format changes character: subnormal range, the
+    # smallest normal, and the overflow threshold 65520
+    dense = [np.arange(np.float32(a).view(np.uint32), np.float32(b).view(np.uint32), step, dtype=np.uint64)
+             for a, b, step in ((2.0 ** -27, 2.0 ** -13, 97), (65400.0, 65600.0, 1), (2.0 ** -15, 2.0 ** -14 * 1.01, 3))]
+    bits = np.concatenate([bits] + [d.astype(np.uint32) for d in dense] +
+                          [d.astype(np.uint32) | np.uint32(0x80000000) for d in dense])
+    got = oc.f32_bits_to_f16(bits)
+    f = bits.view(np.float32)
+    with np.errstate(over="ignore"):
+        want = f.astype(np.float16).view(np.uint16)
+    nan = np.isnan(f)
+    assert np.array_equal(got[~nan], want[~nan])
+    g = got[nan]
+    assert np.all((g & 0x7C00) == 0x7C00) and np.all((g & 0x03FF) != 0)
+
+
+def test_f16_rounding_hand_values():
+    r = lambda x: int(oc.f32_bits_to_f16(np.array([x], dtype=np.float32).view(np.uint32))[0])
+    assert r(1.0) == 0x3C00 and r(-2.0) == 0xC000
+    assert r(65504.0) == 0x7BFF                   # largest finite
+    assert r(65519.99) == 0x7BFF and r(65520.0) == 0x7C00      # halfway to 2^16 ties to "even" = infinity
+    assert r(2.0 ** -24) == 0x0001                # smallest subnormal
+    assert r(2.0 ** -25) == 0x0000                # tie with zero -> even
+    assert r(2.0 ** -25 * 1.0000001) == 0x0001
+    assert r(2.0 ** -14) == 0x0400                # smallest normal
+    assert r(1.0 + 2.0 ** -11) == 0x3C00 and r(1.0 + 3 * 2.0 ** -11) == 0x3C02   # ties to even
+
+
+def test_allreduce_f16_equals_torch_cpu_and_exact_rational():
+    n, count = 8, 40009
+    bufs = [wl.random_bits(count, torch.float16, 300 + r, finite_only=True) for r in range(n)]
+    for r in range(n):   # bring most exponents within reach of each other
+        f = bufs[r].float()
+        mid = torch.ldexp(torch.frexp(f)[0], torch.randint(-2, 3, (count,), generator=torch.Generator().manual_seed(r)))
+        f[: count - 2000] = mid[: count - 2000]
+        bufs[r] = f.to(torch.float16)
+    want_t = torch_formulation(bufs)
+    got = oc.allreduce([wl.to_numpy_bits(b) for b in bufs])
+    nan = torch.isnan(want_t).numpy()
+    assert np.array_equal(got.view(np.uint16)[~nan], want_t.numpy().view(np.uint16)[~nan])
+    assert np.all(np.isnan(got[nan]))
+    # brute force on a sample, last 2000 columns (raw exponents) included
+    idx = list(range(0, 200)) + list(range(count - 100, count))
+    cols = [[bufs[r][i].float().item() for r in range(n)] for i in idx]
+    ref = []
+    for col in cols:
+        acc = Fraction(float(col[0]))
+        for v in col[1:]:
+            if isinstance(acc, float):
+                break
+            acc = round_to_nearest_even(acc + Fraction(float(v)), 23, -126, 127)
+        if not isinstance(acc, float):
+            acc = round_to_nearest_even(acc, 10, -14, 15)
+        ref.append(float(acc))
+    for k, i in enumerate(idx):
+        g = float(got[i])
+        if np.isnan(g) or np.isnan(ref[k]):
+            continue
+        assert g == ref[k], (i, cols[k], g, ref[k])
+
+
+def test_reducescatter_is_the_rank_slice_of_allreduce():
+    n, rc = 8, 5003
+    bufs = [wl.to_numpy_bits(b) for b in wl.make_rank_buffers(wl.config(2), count=n * rc)]
+    full = oc.allreduce(bufs)
+    for rank in (0, 3, 7):
+        assert oc.reducescatter(bufs, rank).tobytes() == full[rank * rc:(rank + 1) * rc].tobytes()
+    ints = [np.arange(n * 4, dtype=np.float32) + 100 * r for r in range(n)]
+    assert oc.reducescatter(ints, 2).tolist() == [float(8 * (8 + j) + 100 * 28) for j in range(4)]
