@@ -15,6 +15,11 @@ A path is identified by its index in C; the path the paper calls NVLink (the
 primary path, which the tuning favours) is passed in as `primary`.  Shares are
 non-negative integers that sum to a fixed total.
 
+Parity unpinned against the paper: it prints no worked numerical example of
+the balancer, and the load percentages of its Table 2 belong to H800 links.
+The pins are hand-executed trajectories of Algorithm 1, the closed-form balance
+point of a pure-bandwidth timing model, and the properties the prose states.
+
 Readings taken where the paper leaves a choice (each is a documented reading,
 not a fact of the paper):
 

@@ -18,6 +18,10 @@
  * the result does not depend on how the message is split over paths, so the
  * oracle has no notion of paths at all.
  *
+ * Parity pins: library routines on special cases, exact rational brute force,
+ * hand-derived values (see the test-suite).  The paper prints no numerical
+ * example of a collective, so nothing here is pinned to a value from the paper.
+ *
  * Plain loops, one element at a time, no blocking or reordering.  The OpenMP
  * pragma only partitions the independent element index over threads.
  *
