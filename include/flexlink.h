@@ -182,6 +182,14 @@ enum flex_host_engine {
                                reduces from a device scratch buffer */
 };
 
+enum flex_slot_sync {
+    FLEX_SYNC_EVENTS = 0,   /* slot hand-over by HIP events (default) */
+    FLEX_SYNC_COUNTERS = 1  /* slot hand-over by the paper's monotonically increasing counters and
+                               stream memory operations (Section "Communicator"): for use i of a slot
+                               the producer waits semEmpty >= i, fills the slot, writes semFull = i+1;
+                               the consumer waits semFull >= i+1, drains it, writes semEmpty = i+1 */
+};
+
 typedef struct flex_config {
     uint64_t chunk_bytes;        /* transit buffer bytes per peer and pipeline step (paper: 4 MB; default
                                     4 MiB); one pinned slot holds (nranks-1) * chunk_bytes */
@@ -210,7 +218,7 @@ typedef struct flex_config {
     uint32_t min_step_bytes;     /* ... but no step is shorter than this per peer (default 256 KiB) */
     uint32_t tune_accept_check;  /* 1 (default): flex_comm_tune keeps the tuned split only if it finishes
                                     sooner than the device path alone, else reverts to device-only */
-    uint32_t reserved;
+    uint32_t slot_sync;          /* flex_slot_sync (default FLEX_SYNC_EVENTS) */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

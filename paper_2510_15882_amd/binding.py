@@ -22,6 +22,7 @@ FLEX_PATH_DEVICE, FLEX_PATH_HOST = 0, 1
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
 FLEX_ENGINE_KERNEL, FLEX_ENGINE_SDMA = 0, 1
+FLEX_SYNC_EVENTS, FLEX_SYNC_COUNTERS = 0, 1
 
 u32, u64, i32, f64 = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double
 
@@ -58,7 +59,7 @@ class Config(_Struct):
                 ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
                 ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("pipeline_depth", u32), ("min_step_bytes", u32),
-                ("tune_accept_check", u32), ("reserved", u32),
+                ("tune_accept_check", u32), ("slot_sync", u32),
                 ("balancer", BalancerCfg)]
 
 

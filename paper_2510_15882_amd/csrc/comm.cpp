@@ -97,6 +97,10 @@ struct flex_comm {
     hipStream_t s_d2h = nullptr, s_h2d = nullptr;
     std::vector<void*> pinned;
     std::vector<hipEvent_t> ev_full, ev_empty;
+    // FLEX_SYNC_COUNTERS: one pair of 32-bit counters per slot (signal memory) and
+    // how often each slot has been used so far
+    std::vector<uint32_t*> sem_full, sem_empty;
+    std::vector<uint32_t> slot_uses;
     uint64_t chunk_seq = 0;  // chunks staged since creation; slot = seq % num_slots
 
     char* scratch = nullptr;
@@ -155,17 +159,29 @@ struct flex_comm {
                 up_dst[j] = base + (size_t)j * cfg.chunk_bytes;
                 nn[j] = n;
             }
-            // producer stage
-            if (chunk_seq >= nslots) HIP_TRY(hipStreamWaitEvent(s_d2h, ev_empty[slot], 0));
+            const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
+            const uint32_t use = counters ? slot_uses[slot] : 0;  // this is use number `use` of the slot
+            // producer stage: the slot must have been drained by its previous use
+            if (counters) {
+                if (use > 0)
+                    HIP_TRY(hipStreamWaitValue32(s_d2h, sem_empty[slot], use, hipStreamWaitValueGte, 0xFFFFFFFFu));
+            } else if (chunk_seq >= nslots) {
+                HIP_TRY(hipStreamWaitEvent(s_d2h, ev_empty[slot], 0));
+            }
             if (kernels) {
                 LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, host_copy_shape, s_d2h));
             } else {
                 for (int j = 0; j < job.npeers; ++j)
                     HIP_TRY(hipMemcpyAsync(up_dst[j], up_src[j], n, hipMemcpyDeviceToHost, s_d2h));
             }
-            HIP_TRY(hipEventRecord(ev_full[slot], s_d2h));
-            // consumer stage
-            HIP_TRY(hipStreamWaitEvent(s_h2d, ev_full[slot], 0));
+            // hand the filled slot over to the consumer stage
+            if (counters) {
+                HIP_TRY(hipStreamWriteValue32(s_d2h, sem_full[slot], use + 1, 0));
+                HIP_TRY(hipStreamWaitValue32(s_h2d, sem_full[slot], use + 1, hipStreamWaitValueGte, 0xFFFFFFFFu));
+            } else {
+                HIP_TRY(hipEventRecord(ev_full[slot], s_d2h));
+                HIP_TRY(hipStreamWaitEvent(s_h2d, ev_full[slot], 0));
+            }
             if (kernels && job.reduce) {
                 // the reduce kernel reads the peers straight from the pinned slot
                 const void* in[FLEX_MAX_RANKS];
@@ -186,7 +202,12 @@ struct flex_comm {
                 for (int j = 0; j < job.npeers; ++j)
                     HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, s_h2d));
             }
-            HIP_TRY(hipEventRecord(ev_empty[slot], s_h2d));
+            if (counters) {
+                HIP_TRY(hipStreamWriteValue32(s_h2d, sem_empty[slot], use + 1, 0));
+                slot_uses[slot] = use + 1;
+            } else {
+                HIP_TRY(hipEventRecord(ev_empty[slot], s_h2d));
+            }
             ++chunk_seq;
         }
         if (!kernels && job.reduce) {
@@ -567,6 +588,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->pipeline_depth = 4;
     cfg->min_step_bytes = 256u << 10;
     cfg->tune_accept_check = 1;
+    cfg->slot_sync = FLEX_SYNC_EVENTS;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -593,7 +615,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     }
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
-        c.host_engine > FLEX_ENGINE_SDMA || c.host_blocks < 1 || c.host_blocks > 65536 || c.pipeline_depth < 1 ||
+        c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 || c.host_blocks > 65536 || c.pipeline_depth < 1 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -644,6 +666,26 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
             e = nullptr;
             CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             m->ev_empty.push_back(e);
+            if (c.slot_sync == FLEX_SYNC_COUNTERS) {
+                // stream memory operations need signal memory, 8 bytes per allocation
+                for (auto* vec : {&m->sem_full, &m->sem_empty}) {
+                    uint32_t* sem = nullptr;
+                    CREATE_TRY(hipExtMallocWithFlags((void**)&sem, 8, hipMallocSignalMemory));
+                    vec->push_back(sem);
+                    CREATE_TRY(hipMemset(sem, 0, 8));
+                }
+                m->slot_uses.push_back(0);
+            }
+        }
+        if (c.slot_sync == FLEX_SYNC_COUNTERS) {
+            int can = 0;
+            CREATE_TRY(hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, m->device));
+            if (!can) {
+                flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_create: device has no stream wait-value support");
+                flex_comm_destroy(m);
+                return FLEX_ERR_UNSUPPORTED;
+            }
+            CREATE_TRY(hipDeviceSynchronize());
         }
         // scratch: per peer, the largest host part a call may have (rounded up
         // by one alignment quantum of the widest element and to 256 bytes)
@@ -678,6 +720,8 @@ int flex_comm_destroy(flex_comm_t* m) {
     }
     for (auto e : m->ev_full) (void)hipEventDestroy(e);
     for (auto e : m->ev_empty) (void)hipEventDestroy(e);
+    for (auto p : m->sem_full) (void)hipFree(p);
+    for (auto p : m->sem_empty) (void)hipFree(p);
     for (auto p : m->pinned) (void)hipHostFree(p);
     if (m->scratch) (void)hipFree(m->scratch);
     if (m->t0) (void)hipEventDestroy(m->t0);

@@ -295,6 +295,43 @@ def test_allgather_bits_do_not_depend_on_split_chunk_or_rank(engine):
 
 
 @pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("collective", ["allreduce", "allgather"])
+def test_counter_handshake_gives_the_same_bits(engine, collective):
+    # slots handed over by monotonically increasing counters and stream memory
+    # operations instead of events; small chunks so that every slot is reused
+    # many times within a call and across calls
+    count = (1 << 20) + 4096 + 3
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want = oracle_allreduce(bufs) if collective == "allreduce" else oracle_allgather(bufs)
+    for slots in (1, 2, 3):
+        with Comm(max_host_units=10000, chunk_bytes=64 << 10, num_slots=slots, host_engine=engine,
+                  slot_sync=fx.FLEX_SYNC_COUNTERS, min_step_bytes=16 << 10) as comm:
+            for call, units in enumerate((300, 2200, 1, 10000, 300)):
+                say("counters", collective, engine, slots, units)
+                if collective == "allreduce":
+                    fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+                    out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+                    fx.flex_allreduce_local(comm, bufs, out)
+                    torch.cuda.synchronize()
+                    assert_same_bits(out, want, "slots %d units %d" % (slots, units))
+                else:
+                    fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+                    out = torch.zeros(8 * count, dtype=torch.bfloat16, device=DEV)
+                    fx.flex_allgather_local(comm, bufs, out)
+                    torch.cuda.synchronize()
+                    assert wl.to_numpy_bits(out).tobytes() == want.tobytes(), (slots, units)
+            # and queued back to back without host synchronisation
+            if collective == "allreduce":
+                fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 700)
+                outs = [torch.zeros(count, dtype=torch.bfloat16, device=DEV) for _ in range(12)]
+                for o in outs:
+                    fx.flex_allreduce_local(comm, bufs, o)
+                torch.cuda.synchronize()
+                for k, o in enumerate(outs):
+                    assert_same_bits(o, want, "queued call %d" % k)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
 def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
     # many split calls queued without host synchronisation, staging slots and
     # scratch reused every call: every output must carry the same bits
