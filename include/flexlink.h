@@ -15,6 +15,13 @@
  *   FLEX_PATH_HOST    the host-staged path of Section "Communicator": peer
  *                     data goes device -> pinned host buffer -> device through
  *                     a double-buffered pipeline on side streams.
+ *   FLEX_PATH_HOST2   optional (num_aux_paths = 2): a second host-staged path
+ *                     with its own pinned ring and streams, driven by the other
+ *                     engine (copy kernels vs DMA engines).  It shares the PCIe
+ *                     link with FLEX_PATH_HOST the way the paper's RDMA NIC
+ *                     shares the PCIe switch with its PCIe path (Section
+ *                     "Observation: Inefficiency of Intra-node PCIe
+ *                     Communication"), and gives the balancer three paths.
  *
  * General conventions
  *   - Every function returns a flex_status code (0 = FLEX_OK) unless stated
@@ -62,7 +69,7 @@ enum flex_status {
 enum flex_dtype { FLEX_F32 = 0, FLEX_BF16 = 1, FLEX_F16 = 2 };
 enum flex_op { FLEX_SUM = 0 };
 enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1, FLEX_REDUCESCATTER = 2 };
-enum flex_path { FLEX_PATH_DEVICE = 0, FLEX_PATH_HOST = 1 };
+enum flex_path { FLEX_PATH_DEVICE = 0, FLEX_PATH_HOST = 1, FLEX_PATH_HOST2 = 2 };
 enum flex_split_mode { FLEX_SPLIT_STATIC = 0, FLEX_SPLIT_ADAPTIVE = 1 };
 enum flex_balancer_stage { FLEX_STAGE_TUNING = 1, FLEX_STAGE_RUNTIME = 2 };
 
@@ -171,6 +178,21 @@ int flex_balancer_destroy(flex_balancer_t* b);
 int flex_partition(uint64_t count, uint32_t host_units, uint32_t share_total,
                    uint32_t align_elems, uint64_t min_count, uint64_t* split_out);
 
+/* The same partition for npaths paths (1..FLEX_MAX_PATHS).
+ *   units      host array of npaths shares; units[0] (the primary path) is
+ *              ignored: the primary path gets what the others leave.
+ *   start_out  host array of npaths + 1 element offsets: path p carries
+ *              [start_out[p], start_out[p+1]); start_out[0] = 0,
+ *              start_out[npaths] = count.
+ * The last path takes the end of the message, the one before it the piece in
+ * front of that, and so on, each by the rule of flex_partition (owed
+ * floor(count * units[p] / share_total), start rounded down to align_elems,
+ * never empty for a non-zero share).  With npaths = 2 it gives flex_partition's
+ * cut.  Errors: INVALID_ARG (null, npaths out of range, shares above
+ * share_total, zero share_total or align_elems). */
+int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint32_t share_total,
+                         uint32_t align_elems, uint64_t min_count, uint64_t* start_out);
+
 /* ------------------------------------------------------------------------
  * Communicator (paper: Section "Communicator").
  * ---------------------------------------------------------------------- */
@@ -219,6 +241,9 @@ typedef struct flex_config {
     uint32_t tune_accept_check;  /* 1 (default): flex_comm_tune keeps the tuned split only if it finishes
                                     sooner than the device path alone, else reverts to device-only */
     uint32_t slot_sync;          /* flex_slot_sync (default FLEX_SYNC_EVENTS) */
+    uint32_t num_aux_paths;      /* host-staged paths: 1 (default) = FLEX_PATH_HOST with host_engine;
+                                    2 = also FLEX_PATH_HOST2 with the other engine */
+    uint32_t reserved;
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 
@@ -234,6 +259,10 @@ typedef struct flex_stats {
     uint32_t static_host_units;
     double last_time_s[FLEX_MAX_PATHS]; /* latest per-path completion times read back (0 = none) */
     double mean_time_s[FLEX_MAX_PATHS]; /* mean over all samples */
+    uint32_t npaths;                    /* 1 + number of host-staged paths of this communicator */
+    uint32_t static_units[FLEX_MAX_PATHS]; /* static shares per path ([0] unused) */
+    uint32_t reserved;
+    uint64_t last_start[FLEX_MAX_PATHS];   /* last call: first element of each path's piece */
     flex_balancer_state_t balancer;     /* state for the size class of the queried message
                                            (npaths == 0 if that class has none) */
 } flex_stats_t;
@@ -344,10 +373,17 @@ int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void
  * Errors: INVALID_ARG (coll, mode, host_units > max_host_units). */
 int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units);
 
+/* The same for communicators with two host-staged paths.
+ *   aux_units  host array of naux (0..FLEX_MAX_PATHS-1) shares, aux_units[a] for
+ *              path 1 + a; paths beyond naux get 0.  Read only in static mode.
+ * Errors: INVALID_ARG (as flex_set_split; a non-zero share for a path the
+ * communicator does not have; shares summing above share_total). */
+int flex_set_split_paths(flex_comm_t* comm, int coll, int mode, const uint32_t* aux_units, int naux);
+
 /* Stage 1 on the real hardware (paper: Section "Stage 1: Initial
  * Coarse-Grained Tuning").  Blocking.  Runs collective `coll` on the given
  * buffers repeatedly: first to measure each path's rate (device path alone;
- * host path at probe_units), then Algorithm 1 with MeasurePathTimings = median
+ * each host path at probe_units with the other idle), then Algorithm 1 with MeasurePathTimings = median
  * of tune_reps calls, until the balancer leaves Stage 1.  Then, unless
  * tune_accept_check is 0 or the host path was already drained, the balanced
  * split is timed once more against the device path alone and reverted to
@@ -363,8 +399,9 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
 /* Install explicit shares for the size class of a message of `count` elements of
  * `dtype` (for example shares saved from an earlier flex_comm_tune): the class
  * gets a balancer in Stage 2 holding them, marked as tuned.
- *   shares  host array of 2 units {device, host} summing to share_total;
- *           a path given 0 units is inactive.
+ *   shares  host array of one share per path of the communicator ({device,
+ *           host}, or {device, host, host2} with num_aux_paths = 2) summing to
+ *           share_total; a path given 0 units is inactive.
  * Errors: INVALID_ARG (null, unknown collective, sum != share_total, host share
  * above max_host_units), UNSUPPORTED (dtype). */
 int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares);

@@ -32,3 +32,33 @@ def partition(count, host_units, total=10000, align=2048, min_count=32768):
     if split == count:
         split = count - align
     return split
+
+
+def partition_paths(count, units, total=10000, align=2048, min_count=32768):
+    """Several auxiliary paths.  units[p] is path p's share (units[0], the
+    primary path's, is not used: it gets what is left).  Returns the list
+    `start` of len(units) + 1 offsets: path p carries [start[p], start[p+1]).
+
+    Reading: the pieces are laid out in path order; they are cut from the end
+    of the message backwards, each by the two-path rule applied to what is
+    still unassigned in front of it: owed = floor(count * units[p] / total)
+    elements, the piece's start rounded down to a multiple of `align` (not
+    below 0), one alignment quantum at least for a non-zero share while
+    anything is left.  Messages shorter than `min_count` or `align` are not
+    split."""
+    if sum(units[1:]) > total or min(units) < 0:
+        raise ValueError("shares out of range")
+    n = len(units)
+    start = [0] * (n + 1)
+    start[n] = count
+    end = count
+    for p in range(n - 1, 0, -1):
+        s = end
+        if units[p] > 0 and count >= min_count and count >= align:
+            owed = (count * units[p]) // total
+            s = ((end - owed) // align) * align if end > owed else 0
+            if s == end:                       # rounding left the piece empty
+                s = ((end - 1) // align) * align if end >= align else 0
+        start[p] = s
+        end = s
+    return start

@@ -18,7 +18,7 @@ FLEX_OK, FLEX_ERR_INVALID_ARG, FLEX_ERR_UNSUPPORTED, FLEX_ERR_HIP, FLEX_ERR_NOME
 FLEX_F32, FLEX_BF16, FLEX_F16 = 0, 1, 2
 FLEX_SUM = 0
 FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER = 0, 1, 2
-FLEX_PATH_DEVICE, FLEX_PATH_HOST = 0, 1
+FLEX_PATH_DEVICE, FLEX_PATH_HOST, FLEX_PATH_HOST2 = 0, 1, 2
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
 FLEX_ENGINE_KERNEL, FLEX_ENGINE_SDMA = 0, 1
@@ -59,7 +59,7 @@ class Config(_Struct):
                 ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
                 ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("pipeline_depth", u32), ("min_step_bytes", u32),
-                ("tune_accept_check", u32), ("slot_sync", u32),
+                ("tune_accept_check", u32), ("slot_sync", u32), ("num_aux_paths", u32), ("reserved", u32),
                 ("balancer", BalancerCfg)]
 
 
@@ -67,6 +67,8 @@ class Stats(_Struct):
     _fields_ = [("calls", u64), ("split_calls", u64), ("samples", u64), ("blocking_reads", u64),
                 ("last_count", u64), ("last_split", u64), ("mode", u32), ("static_host_units", u32),
                 ("last_time_s", f64 * FLEX_MAX_PATHS), ("mean_time_s", f64 * FLEX_MAX_PATHS),
+                ("npaths", u32), ("static_units", u32 * FLEX_MAX_PATHS), ("reserved", u32),
+                ("last_start", u64 * FLEX_MAX_PATHS),
                 ("balancer", BalancerState)]
 
 
@@ -111,6 +113,8 @@ def lib():
         "flex_balancer_get": [vp, P(BalancerState)],
         "flex_balancer_destroy": [vp],
         "flex_partition": [u64, u32, u32, u32, u64, P(u64)],
+        "flex_partition_paths": [u64, P(u32), ci, u32, u32, u64, P(u64)],
+        "flex_set_split_paths": [vp, ci, ci, P(u32), ci],
         "flex_config_default": [P(Config)],
         "flex_comm_create": [pvp, ci, ci, sz, P(Config)],
         "flex_comm_destroy": [vp],
@@ -294,8 +298,21 @@ def flex_comm_tune(comm, coll, rank_bufs, out, count=None, stream=None):
     return res
 
 
+def flex_partition_paths(count, units, share_total=10000, align_elems=2048, min_count=32768):
+    n = len(units)
+    arr = (u32 * n)(*units)
+    out = (u64 * (n + 1))()
+    _check(lib().flex_partition_paths(count, arr, n, share_total, align_elems, min_count, out))
+    return list(out)
+
+
+def flex_set_split_paths(comm, coll, mode, aux_units=()):
+    arr = (u32 * max(len(aux_units), 1))(*aux_units)
+    _check(lib().flex_set_split_paths(comm, coll, mode, arr, len(aux_units)))
+
+
 def flex_comm_set_shares(comm, coll, count, dtype, shares):
-    arr = (u32 * 2)(*shares)
+    arr = (u32 * FLEX_MAX_PATHS)(*shares)
     _check(lib().flex_comm_set_shares(comm, coll, count, dtype_code(dtype), arr))
 
 

@@ -283,4 +283,16 @@ int flex_partition(uint64_t count, uint32_t host_units, uint32_t share_total, ui
     return FLEX_OK;
 }
 
+int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint32_t share_total,
+                         uint32_t align_elems, uint64_t min_count, uint64_t* start_out) {
+    if (!units || !start_out || npaths < 1 || npaths > FLEX_MAX_PATHS || share_total == 0 || align_elems == 0)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_partition_paths: argument out of range");
+    uint64_t sum = 0;
+    for (int p = 1; p < npaths; ++p) sum += units[p];
+    if (sum > share_total)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_partition_paths: shares exceed share_total");
+    flex::partition_paths(count, units, npaths, share_total, align_elems, min_count, start_out);
+    return FLEX_OK;
+}
+
 }  // extern "C"

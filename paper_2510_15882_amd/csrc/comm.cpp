@@ -1,5 +1,5 @@
-// Communicator: partitions each collective over the device path and the
-// host-staged path, runs both concurrently (fork/join by events), and feeds the
+// Communicator: partitions each collective over the device path and one or two
+// host-staged paths, runs them concurrently (fork/join by events), and feeds the
 // per-path completion times back to the balancer (the paper's Evaluator).
 // Paper: Design; Section "Communicator"; Section "Two-Stage Load Balancing
 // Strategy".
@@ -48,29 +48,32 @@ int fail(int status, const char* fmt, ...) {
 namespace {
 
 constexpr size_t kRingSize = 256;  // timing records that may be in flight
+constexpr int kMaxAux = FLEX_MAX_PATHS - 1;
 
 // One split call's events; the Evaluator reads the elapsed times back later.
 struct TimingRecord {
-    hipEvent_t fork = nullptr, dev_done = nullptr, host_done = nullptr;
+    hipEvent_t fork = nullptr;
+    hipEvent_t done[FLEX_MAX_PATHS] = {nullptr, nullptr, nullptr, nullptr};
+    uint32_t used_mask = 0;  // bit p: path p carried part of the message
     int coll = 0;
     int size_class = 0;
     bool adaptive = false;
-    bool has_device_part = false;
     uint64_t generation = 0;  // balancer generation the call's shares came from
 };
 
 struct SizeClass {
     flex::Balancer bal;
-    bool tuned = false;       // produced by flex_comm_tune (else borrowed)
+    bool tuned = false;       // produced by flex_comm_tune / flex_comm_set_shares (else borrowed)
     uint64_t generation = 0;  // bumped whenever the shares change
 };
 
 struct CollState {
     uint32_t mode = FLEX_SPLIT_STATIC;
-    uint32_t static_units = 0;
+    uint32_t static_units[FLEX_MAX_PATHS] = {0, 0, 0, 0};  // [0] unused
     std::map<int, SizeClass> classes;
     uint64_t calls = 0, split_calls = 0, samples = 0;
-    uint64_t last_count = 0, last_split = 0;
+    uint64_t last_count = 0;
+    uint64_t last_start[FLEX_MAX_PATHS + 1] = {0, 0, 0, 0, 0};
     double last_t[FLEX_MAX_PATHS] = {0, 0, 0, 0};
     double sum_t[FLEX_MAX_PATHS] = {0, 0, 0, 0};
 };
@@ -84,6 +87,58 @@ int size_class_of(size_t bytes) {
     return c;
 }
 
+double median_of(std::vector<double> v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return (n & 1) ? v[n / 2] : (v[n / 2 - 1] + v[n / 2]) / 2.0;
+}
+
+// What the consumer stage of a host path does with a step once it sits in the
+// pinned slot.
+struct HostJob {
+    int npeers = 0;
+    const char* peer_src[FLEX_MAX_RANKS];  // start of each peer's part (device memory)
+    // AllGather: where each peer's part goes.  DMA-engine reduce: device scratch.
+    char* peer_dst[FLEX_MAX_RANKS];
+    // reduce in rank order into out_part; the local rank's part is read in place
+    bool reduce = false;
+    int dtype = 0;
+    int nranks = 0;
+    int local_index = 0;  // position of the local rank among the nranks inputs
+    const char* local_src = nullptr;
+    char* out_part = nullptr;
+};
+
+// One host-staged path: a ring of pinned slots, a producer and a consumer
+// stream, and the slot hand-over state.
+struct HostPath {
+    int engine = FLEX_ENGINE_KERNEL;
+    hipStream_t s_up = nullptr, s_down = nullptr;  // producer / consumer stage
+    std::vector<void*> pinned;
+    std::vector<hipEvent_t> ev_full, ev_empty;
+    // FLEX_SYNC_COUNTERS: one pair of 32-bit counters per slot (signal memory) and
+    // how often each slot has been used so far
+    std::vector<uint32_t*> sem_full, sem_empty;
+    std::vector<uint32_t> slot_uses;
+    uint64_t chunk_seq = 0;  // steps staged since creation; slot = seq % num_slots
+    char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
+    size_t scratch_stride = 0;
+
+    void destroy() {
+        if (s_up) (void)hipStreamSynchronize(s_up);
+        if (s_down) (void)hipStreamSynchronize(s_down);
+        for (auto e : ev_full) (void)hipEventDestroy(e);
+        for (auto e : ev_empty) (void)hipEventDestroy(e);
+        for (auto p : sem_full) (void)hipFree(p);
+        for (auto p : sem_empty) (void)hipFree(p);
+        for (auto p : pinned) (void)hipHostFree(p);
+        if (scratch) (void)hipFree(scratch);
+        if (s_up) (void)hipStreamDestroy(s_up);
+        if (s_down) (void)hipStreamDestroy(s_down);
+        *this = HostPath();
+    }
+};
+
 }  // namespace
 
 struct flex_comm {
@@ -92,19 +147,11 @@ struct flex_comm {
     size_t max_bytes = 0;
     flex_config_t cfg;
     flex::LaunchShape reduce_shape, copy_shape;            // device path
-    flex::LaunchShape host_reduce_shape, host_copy_shape;  // host path (kernel engine): few workgroups
+    flex::LaunchShape host_reduce_shape, host_copy_shape;  // host paths (kernel engine): few workgroups
 
-    hipStream_t s_d2h = nullptr, s_h2d = nullptr;
-    std::vector<void*> pinned;
-    std::vector<hipEvent_t> ev_full, ev_empty;
-    // FLEX_SYNC_COUNTERS: one pair of 32-bit counters per slot (signal memory) and
-    // how often each slot has been used so far
-    std::vector<uint32_t*> sem_full, sem_empty;
-    std::vector<uint32_t> slot_uses;
-    uint64_t chunk_seq = 0;  // chunks staged since creation; slot = seq % num_slots
-
-    char* scratch = nullptr;
-    size_t scratch_stride = 0;  // bytes of scratch per peer
+    int naux = 0;  // auxiliary (host-staged) paths: path index 1 + a
+    HostPath aux[kMaxAux];
+    int npaths() const { return 1 + naux; }
 
     std::vector<TimingRecord> ring;
     size_t ring_head = 0, ring_count = 0;
@@ -114,43 +161,29 @@ struct flex_comm {
     CollState coll[3];  // indexed by flex_coll
 
     // ---- host-staged path --------------------------------------------------
-    // What the consumer stage does with a step once it sits in the pinned slot.
-    struct HostJob {
-        int npeers = 0;
-        const char* peer_src[FLEX_MAX_RANKS];  // start of each peer's host part (device memory)
-        // AllGather: where each peer's host part goes
-        char* peer_dst[FLEX_MAX_RANKS];
-        // AllReduce: reduce in rank order into out_tail; the local rank's part is read in place
-        bool reduce = false;
-        int dtype = 0;
-        int local_index = 0;  // position of the local rank among the nranks inputs
-        const char* local_src = nullptr;
-        char* out_tail = nullptr;
-    };
-
-    // Move `bytes` bytes per peer through the ring of pinned slots, step by
-    // step: producer stage (device -> pinned slot) on s_d2h, consumer stage
-    // (pinned slot -> device) on s_h2d.  A slot is refilled only after the
-    // consumer that drained it (ev_empty) and drained only after the producer
-    // that filled it (ev_full), so the producer of one step overlaps the
-    // consumer of the previous one: PCIe carries both directions at once.  The
-    // slot of a step is its sequence number modulo the ring size, counted since
-    // the communicator was created.
-    int host_path(const HostJob& job, size_t bytes) {
-        const size_t nslots = pinned.size();
+    // Move `bytes` bytes per peer through the path's ring of pinned slots, step
+    // by step: producer stage (device -> pinned slot) on s_up, consumer stage
+    // (pinned slot -> device) on s_down.  A slot is refilled only after the
+    // consumer that drained it and drained only after the producer that filled
+    // it, so the producer of one step overlaps the consumer of the previous one:
+    // PCIe carries both directions at once.  The slot of a step is its sequence
+    // number modulo the ring size, counted since the communicator was created.
+    int host_path(HostPath& hp, const HostJob& job, size_t bytes) {
+        const size_t nslots = hp.pinned.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
-        // even steps: no short remainder step, and a short host part is still cut
-        // into a few steps so that the two stages overlap
+        // even steps: no short remainder step, and a short part is still cut into
+        // a few steps so that the two stages overlap
         size_t nsteps = (bytes + cfg.chunk_bytes - 1) / cfg.chunk_bytes;
         size_t want = std::min<size_t>(cfg.pipeline_depth, bytes / std::max<size_t>(cfg.min_step_bytes, 1));
         nsteps = std::max<size_t>(std::max(nsteps, want), 1);
-        size_t step = ((bytes + nsteps - 1) / nsteps + 255) / 256 * 256;
-        const bool kernels = cfg.host_engine == FLEX_ENGINE_KERNEL;
+        const size_t step = ((bytes + nsteps - 1) / nsteps + 255) / 256 * 256;
+        const bool kernels = hp.engine == FLEX_ENGINE_KERNEL;
+        const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
 
         for (size_t off = 0; off < bytes; off += step) {
             const size_t n = std::min(step, bytes - off);
-            const size_t slot = chunk_seq % nslots;
-            char* base = (char*)pinned[slot];
+            const size_t slot = hp.chunk_seq % nslots;
+            char* base = (char*)hp.pinned[slot];
             const void* up_src[FLEX_MAX_RANKS];
             void* up_dst[FLEX_MAX_RANKS];
             uint64_t nn[FLEX_MAX_RANKS];
@@ -159,37 +192,38 @@ struct flex_comm {
                 up_dst[j] = base + (size_t)j * cfg.chunk_bytes;
                 nn[j] = n;
             }
-            const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
-            const uint32_t use = counters ? slot_uses[slot] : 0;  // this is use number `use` of the slot
+            const uint32_t use = counters ? hp.slot_uses[slot] : 0;  // this is use number `use` of the slot
             // producer stage: the slot must have been drained by its previous use
             if (counters) {
                 if (use > 0)
-                    HIP_TRY(hipStreamWaitValue32(s_d2h, sem_empty[slot], use, hipStreamWaitValueGte, 0xFFFFFFFFu));
-            } else if (chunk_seq >= nslots) {
-                HIP_TRY(hipStreamWaitEvent(s_d2h, ev_empty[slot], 0));
+                    HIP_TRY(hipStreamWaitValue32(hp.s_up, hp.sem_empty[slot], use, hipStreamWaitValueGte,
+                                                 0xFFFFFFFFu));
+            } else if (hp.chunk_seq >= nslots) {
+                HIP_TRY(hipStreamWaitEvent(hp.s_up, hp.ev_empty[slot], 0));
             }
             if (kernels) {
-                LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, host_copy_shape, s_d2h));
+                LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, host_copy_shape, hp.s_up));
             } else {
                 for (int j = 0; j < job.npeers; ++j)
-                    HIP_TRY(hipMemcpyAsync(up_dst[j], up_src[j], n, hipMemcpyDeviceToHost, s_d2h));
+                    HIP_TRY(hipMemcpyAsync(up_dst[j], up_src[j], n, hipMemcpyDeviceToHost, hp.s_up));
             }
             // hand the filled slot over to the consumer stage
             if (counters) {
-                HIP_TRY(hipStreamWriteValue32(s_d2h, sem_full[slot], use + 1, 0));
-                HIP_TRY(hipStreamWaitValue32(s_h2d, sem_full[slot], use + 1, hipStreamWaitValueGte, 0xFFFFFFFFu));
+                HIP_TRY(hipStreamWriteValue32(hp.s_up, hp.sem_full[slot], use + 1, 0));
+                HIP_TRY(hipStreamWaitValue32(hp.s_down, hp.sem_full[slot], use + 1, hipStreamWaitValueGte,
+                                             0xFFFFFFFFu));
             } else {
-                HIP_TRY(hipEventRecord(ev_full[slot], s_d2h));
-                HIP_TRY(hipStreamWaitEvent(s_h2d, ev_full[slot], 0));
+                HIP_TRY(hipEventRecord(hp.ev_full[slot], hp.s_up));
+                HIP_TRY(hipStreamWaitEvent(hp.s_down, hp.ev_full[slot], 0));
             }
             if (kernels && job.reduce) {
                 // the reduce kernel reads the peers straight from the pinned slot
                 const void* in[FLEX_MAX_RANKS];
                 int j = 0;
-                for (int r = 0; r < nranks; ++r)
+                for (int r = 0; r < job.nranks; ++r)
                     in[r] = (r == job.local_index) ? (const void*)(job.local_src + off) : up_dst[j++];
-                LAUNCH_TRY(flex::launch_reduce_n(in, nranks, job.out_tail + off, n / es, job.dtype,
-                                                 host_reduce_shape, s_h2d));
+                LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part + off, n / es, job.dtype,
+                                                 host_reduce_shape, hp.s_down));
             } else if (kernels) {
                 const void* dn_src[FLEX_MAX_RANKS];
                 void* dn_dst[FLEX_MAX_RANKS];
@@ -197,26 +231,27 @@ struct flex_comm {
                     dn_src[j] = up_dst[j];
                     dn_dst[j] = job.peer_dst[j] + off;
                 }
-                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, host_copy_shape, s_h2d));
+                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, host_copy_shape, hp.s_down));
             } else {
                 for (int j = 0; j < job.npeers; ++j)
-                    HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, s_h2d));
+                    HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, hp.s_down));
             }
             if (counters) {
-                HIP_TRY(hipStreamWriteValue32(s_h2d, sem_empty[slot], use + 1, 0));
-                slot_uses[slot] = use + 1;
+                HIP_TRY(hipStreamWriteValue32(hp.s_down, hp.sem_empty[slot], use + 1, 0));
+                hp.slot_uses[slot] = use + 1;
             } else {
-                HIP_TRY(hipEventRecord(ev_empty[slot], s_h2d));
+                HIP_TRY(hipEventRecord(hp.ev_empty[slot], hp.s_down));
             }
-            ++chunk_seq;
+            ++hp.chunk_seq;
         }
         if (!kernels && job.reduce) {
             // DMA engine: the peers' parts now sit in device scratch (peer_dst)
             const void* in[FLEX_MAX_RANKS];
             int j = 0;
-            for (int r = 0; r < nranks; ++r)
+            for (int r = 0; r < job.nranks; ++r)
                 in[r] = (r == job.local_index) ? (const void*)job.local_src : (const void*)job.peer_dst[j++];
-            LAUNCH_TRY(flex::launch_reduce_n(in, nranks, job.out_tail, bytes / es, job.dtype, reduce_shape, s_h2d));
+            LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part, bytes / es, job.dtype, reduce_shape,
+                                             hp.s_down));
         }
         return FLEX_OK;
     }
@@ -253,13 +288,16 @@ struct flex_comm {
     }
 
     int consume(TimingRecord& rec) {
-        float ms_dev = 0.f, ms_host = 0.f;
-        if (rec.has_device_part) HIP_TRY(hipEventElapsedTime(&ms_dev, rec.fork, rec.dev_done));
-        HIP_TRY(hipEventElapsedTime(&ms_host, rec.fork, rec.host_done));
+        double T[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+        for (int p = 0; p < npaths(); ++p) {
+            if (!(rec.used_mask & (1u << p))) continue;
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, rec.fork, rec.done[p]));
+            T[p] = ms * 1e-3;
+        }
         CollState& cs = coll[rec.coll];
-        double T[FLEX_MAX_PATHS] = {ms_dev * 1e-3, ms_host * 1e-3, 0, 0};
         ++cs.samples;
-        for (int p = 0; p < 2; ++p) {
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p) {
             cs.last_t[p] = T[p];
             cs.sum_t[p] += T[p];
         }
@@ -267,33 +305,53 @@ struct flex_comm {
             SizeClass* sc = find_class(rec.coll, rec.size_class);
             // a call issued before the last share change says nothing about the new shares
             if (sc && sc->generation == rec.generation && sc->bal.stage == FLEX_STAGE_RUNTIME) {
-                uint32_t before = sc->bal.shares[FLEX_PATH_HOST];
-                if (sc->bal.update(T) && sc->bal.shares[FLEX_PATH_HOST] != before) ++sc->generation;
+                uint32_t before[FLEX_MAX_PATHS];
+                memcpy(before, sc->bal.shares, sizeof before);
+                if (sc->bal.update(T) && memcmp(before, sc->bal.shares, sizeof before) != 0) ++sc->generation;
             }
         }
         return FLEX_OK;
     }
 
-    int poll(bool block) {
-        while (ring_count > 0) {
-            TimingRecord& rec = ring[ring_head];
+    // All of a record's events have completed (block: wait until they have).
+    int record_ready(TimingRecord& rec, bool block, bool* ready) {
+        *ready = true;
+        for (int p = FLEX_MAX_PATHS - 1; p >= 0; --p) {
+            if (!(rec.used_mask & (1u << p))) continue;
             if (block) {
-                HIP_TRY(hipEventSynchronize(rec.host_done));
-                HIP_TRY(hipEventSynchronize(rec.dev_done));
+                HIP_TRY(hipEventSynchronize(rec.done[p]));
             } else {
-                hipError_t q = hipEventQuery(rec.host_done);
-                if (q == hipErrorNotReady) break;
-                if (q != hipSuccess)
-                    return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
-                q = hipEventQuery(rec.dev_done);
-                if (q == hipErrorNotReady) break;
+                hipError_t q = hipEventQuery(rec.done[p]);
+                if (q == hipErrorNotReady) {
+                    *ready = false;
+                    return FLEX_OK;
+                }
                 if (q != hipSuccess)
                     return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
             }
-            int st = consume(rec);
-            ring_head = (ring_head + 1) % kRingSize;
-            --ring_count;
+        }
+        return FLEX_OK;
+    }
+
+    int pop_oldest(bool block, bool* popped) {
+        TimingRecord& rec = ring[ring_head];
+        bool ready = false;
+        int st = record_ready(rec, block, &ready);
+        *popped = false;
+        if (st || !ready) return st;
+        st = consume(rec);
+        ring_head = (ring_head + 1) % kRingSize;
+        --ring_count;
+        *popped = true;
+        return st;
+    }
+
+    int poll(bool block) {
+        while (ring_count > 0) {
+            bool popped = false;
+            int st = pop_oldest(block, &popped);
             if (st) return st;
+            if (!popped) break;
         }
         return FLEX_OK;
     }
@@ -302,12 +360,8 @@ struct flex_comm {
         if (ring_count == kRingSize) {
             // every record is in flight: wait for the oldest one
             ++blocking_reads;
-            TimingRecord& rec = ring[ring_head];
-            HIP_TRY(hipEventSynchronize(rec.host_done));
-            HIP_TRY(hipEventSynchronize(rec.dev_done));
-            int st = consume(rec);
-            ring_head = (ring_head + 1) % kRingSize;
-            --ring_count;
+            bool popped = false;
+            int st = pop_oldest(true, &popped);
             if (st) return st;
         }
         *out = &ring[(ring_head + ring_count) % kRingSize];
@@ -315,18 +369,24 @@ struct flex_comm {
         return FLEX_OK;
     }
 
-    // Host share, in units, that a call of `bytes` per rank uses now.
-    uint32_t units_for_call(int c, size_t bytes, bool* adaptive, SizeClass** sc_out) {
+    // Share, in units, that each auxiliary path of a call of `bytes` per rank
+    // uses now (units[0] is not used).
+    void units_for_call(int c, size_t bytes, uint32_t* units, bool* adaptive, SizeClass** sc_out) {
         CollState& cs = coll[c];
         *adaptive = false;
         *sc_out = nullptr;
-        if (nranks < 2) return 0;
-        if (cs.mode == FLEX_SPLIT_STATIC) return cs.static_units;
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p) units[p] = 0;
+        if (nranks < 2) return;
+        if (cs.mode == FLEX_SPLIT_STATIC) {
+            for (int p = 1; p < npaths(); ++p) units[p] = cs.static_units[p];
+            return;
+        }
         SizeClass* sc = class_for_call(c, size_class_of(bytes));
-        if (!sc || sc->bal.npaths < 2) return 0;
+        if (!sc || sc->bal.npaths < 2) return;
         *adaptive = true;
         *sc_out = sc;
-        return std::min(sc->bal.shares[FLEX_PATH_HOST], cfg.max_host_units);
+        for (int p = 1; p < npaths() && p < sc->bal.npaths; ++p)
+            units[p] = std::min(sc->bal.shares[p], cfg.max_host_units);
     }
 
     int check_device() const {
@@ -335,6 +395,33 @@ struct flex_comm {
         if (cur != device)
             return flex::fail(FLEX_ERR_STATE, "communicator belongs to device %d, current device is %d",
                               device, cur);
+        return FLEX_OK;
+    }
+
+    // Segment starts of a call: path p carries elements [start[p], start[p+1]).
+    bool split_message(int c, size_t count, size_t es, uint64_t* start, bool* adaptive, SizeClass** sc) {
+        uint32_t units[FLEX_MAX_PATHS];
+        units_for_call(c, count * es, units, adaptive, sc);
+        flex::partition_paths(count, units, npaths(), cfg.balancer.share_total, cfg.split_align_elems,
+                              cfg.min_split_bytes / es, start);
+        for (int p = npaths(); p < FLEX_MAX_PATHS; ++p) start[p + 1] = count;
+        CollState& cs = coll[c];
+        cs.last_count = count;
+        for (int p = 0; p <= FLEX_MAX_PATHS; ++p) cs.last_start[p] = start[p];
+        return start[1] < count;  // some auxiliary path carries data
+    }
+
+    int begin_split_call(int c, size_t bytes, bool adaptive, SizeClass* sc, TimingRecord** rec_out) {
+        ++coll[c].split_calls;
+        TimingRecord* rec;
+        int st = acquire_record(&rec);
+        if (st) return st;
+        rec->coll = c;
+        rec->size_class = size_class_of(bytes);
+        rec->adaptive = adaptive;
+        rec->generation = sc ? sc->generation : 0;
+        rec->used_mask = 0;
+        *rec_out = rec;
         return FLEX_OK;
     }
 
@@ -351,7 +438,9 @@ struct flex_comm {
     }
     int validate(const char* who, const void* const* bufs, const void* out, size_t count, int dtype);
     int measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
-                      hipStream_t stream, uint32_t units, double* T);
+                      hipStream_t stream, const uint32_t* units, double* T);
+    int time_device_alone(int c, const void* const* bufs, void* out, size_t count, int dtype,
+                          hipStream_t stream, double* seconds);
 };
 
 int flex_comm::validate(const char* who, const void* const* bufs, const void* out, size_t count,
@@ -405,62 +494,61 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     if (st) return st;
 
     const size_t es = flex::dtype_size(dtype);
+    uint64_t start[FLEX_MAX_PATHS + 1];
     bool adaptive;
     SizeClass* sc;
-    const uint32_t units = units_for_call(c, count * es, &adaptive, &sc);
-    const uint64_t split = flex::partition(count, units, cfg.balancer.share_total, cfg.split_align_elems,
-                                           cfg.min_split_bytes / es);
-    const size_t host_count = count - split;
-    cs.last_count = count;
-    cs.last_split = split;
-
-    if (host_count == 0) {
+    if (!split_message(c, count, es, start, &adaptive, &sc)) {
         LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, count, dtype, reduce_shape, stream));
         return FLEX_OK;
     }
-    if (cfg.host_engine == FLEX_ENGINE_SDMA && host_count * es > scratch_stride)
-        return flex::fail(FLEX_ERR_INVALID_ARG,
-                          "%s: host part of %zu bytes exceeds the scratch sized by max_host_units (%zu bytes per peer)",
-                          who, host_count * es, scratch_stride);
+    for (int a = 0; a < naux; ++a) {
+        const size_t part = (start[a + 2] - start[a + 1]) * es;
+        if (aux[a].engine == FLEX_ENGINE_SDMA && part > aux[a].scratch_stride)
+            return flex::fail(FLEX_ERR_INVALID_ARG,
+                              "%s: host part of %zu bytes exceeds the scratch sized by max_host_units (%zu bytes "
+                              "per peer)", who, part, aux[a].scratch_stride);
+    }
 
-    ++cs.split_calls;
     TimingRecord* rec;
-    st = acquire_record(&rec);
+    st = begin_split_call(c, count * es, adaptive, sc, &rec);
     if (st) return st;
-    rec->coll = c;
-    rec->size_class = size_class_of(count * es);
-    rec->adaptive = adaptive;
-    rec->generation = sc ? sc->generation : 0;
-    rec->has_device_part = split > 0;
 
     // fork
     HIP_TRY(hipEventRecord(rec->fork, stream));
-    HIP_TRY(hipStreamWaitEvent(s_d2h, rec->fork, 0));
 
     // device path: head of the message, straight from HBM
-    if (split > 0) LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, split, dtype, reduce_shape, stream));
-    HIP_TRY(hipEventRecord(rec->dev_done, stream));
-
-    // host path: every peer's tail goes device -> pinned slot -> device and is
-    // reduced in the same rank order; the local contribution never leaves HBM
-    HostJob job;
-    job.reduce = true;
-    job.dtype = dtype;
-    job.local_index = rank;
-    job.local_src = (const char*)bufs[rank] + split * es;
-    job.out_tail = (char*)out + split * es;
-    for (int r = 0; r < nranks; ++r) {
-        if (r == rank) continue;
-        job.peer_src[job.npeers] = (const char*)bufs[r] + split * es;
-        job.peer_dst[job.npeers] = scratch ? scratch + (size_t)job.npeers * scratch_stride : nullptr;
-        ++job.npeers;
+    if (start[1] > 0) {
+        LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, start[1], dtype, reduce_shape, stream));
+        rec->used_mask |= 1u;
     }
-    st = host_path(job, host_count * es);
-    if (st) return st;
-    HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
+    HIP_TRY(hipEventRecord(rec->done[0], stream));
 
-    // join
-    HIP_TRY(hipStreamWaitEvent(stream, rec->host_done, 0));
+    // host paths: every peer's part goes device -> pinned slot -> device and is
+    // reduced in the same rank order; the local contribution never leaves HBM
+    for (int a = 0; a < naux; ++a) {
+        const uint64_t lo = start[a + 1], hi = start[a + 2];
+        if (hi == lo) continue;
+        HostPath& hp = aux[a];
+        HIP_TRY(hipStreamWaitEvent(hp.s_up, rec->fork, 0));
+        HostJob job;
+        job.reduce = true;
+        job.dtype = dtype;
+        job.nranks = nranks;
+        job.local_index = rank;
+        job.local_src = (const char*)bufs[rank] + lo * es;
+        job.out_part = (char*)out + lo * es;
+        for (int r = 0; r < nranks; ++r) {
+            if (r == rank) continue;
+            job.peer_src[job.npeers] = (const char*)bufs[r] + lo * es;
+            job.peer_dst[job.npeers] = hp.scratch ? hp.scratch + (size_t)job.npeers * hp.scratch_stride : nullptr;
+            ++job.npeers;
+        }
+        st = host_path(hp, job, (hi - lo) * es);
+        if (st) return st;
+        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.s_down));
+        rec->used_mask |= 1u << (a + 1);
+        HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));  // join
+    }
     return FLEX_OK;
 }
 
@@ -476,14 +564,10 @@ int flex_comm::allgather(const void* const* slices, void* out, size_t count, int
 
     const size_t es = flex::dtype_size(dtype);
     const size_t slice_bytes = count * es;
+    uint64_t start[FLEX_MAX_PATHS + 1];
     bool adaptive;
     SizeClass* sc;
-    const uint32_t units = units_for_call(FLEX_ALLGATHER, slice_bytes, &adaptive, &sc);
-    const uint64_t split = flex::partition(count, units, cfg.balancer.share_total, cfg.split_align_elems,
-                                           cfg.min_split_bytes / es);
-    const size_t host_bytes = (count - split) * es;
-    cs.last_count = count;
-    cs.last_split = split;
+    const bool split = split_message(FLEX_ALLGATHER, count, es, start, &adaptive, &sc);
 
     const void* src[FLEX_MAX_RANKS];
     void* dst[FLEX_MAX_RANKS];
@@ -491,52 +575,52 @@ int flex_comm::allgather(const void* const* slices, void* out, size_t count, int
     for (int r = 0; r < nranks; ++r) {
         src[r] = slices[r];
         dst[r] = (char*)out + (size_t)r * slice_bytes;
-        bytes[r] = (r == rank) ? slice_bytes : split * es;  // local slice: whole, on the device path
+        bytes[r] = (r == rank) ? slice_bytes : start[1] * es;  // local slice: whole, on the device path
     }
-
-    if (host_bytes == 0) {
+    if (!split) {
         LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
         return FLEX_OK;
     }
 
-    ++cs.split_calls;
     TimingRecord* rec;
-    st = acquire_record(&rec);
+    st = begin_split_call(FLEX_ALLGATHER, slice_bytes, adaptive, sc, &rec);
     if (st) return st;
-    rec->coll = FLEX_ALLGATHER;
-    rec->size_class = size_class_of(slice_bytes);
-    rec->adaptive = adaptive;
-    rec->generation = sc ? sc->generation : 0;
-    rec->has_device_part = true;
-
     HIP_TRY(hipEventRecord(rec->fork, stream));
-    HIP_TRY(hipStreamWaitEvent(s_d2h, rec->fork, 0));
 
     LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
-    HIP_TRY(hipEventRecord(rec->dev_done, stream));
+    rec->used_mask |= 1u;
+    HIP_TRY(hipEventRecord(rec->done[0], stream));
 
-    HostJob job;
-    for (int r = 0; r < nranks; ++r) {
-        if (r == rank) continue;
-        job.peer_src[job.npeers] = (const char*)slices[r] + split * es;
-        job.peer_dst[job.npeers] = (char*)dst[r] + split * es;
-        ++job.npeers;
+    for (int a = 0; a < naux; ++a) {
+        const uint64_t lo = start[a + 1], hi = start[a + 2];
+        if (hi == lo) continue;
+        HostPath& hp = aux[a];
+        HIP_TRY(hipStreamWaitEvent(hp.s_up, rec->fork, 0));
+        HostJob job;
+        for (int r = 0; r < nranks; ++r) {
+            if (r == rank) continue;
+            job.peer_src[job.npeers] = (const char*)slices[r] + lo * es;
+            job.peer_dst[job.npeers] = (char*)dst[r] + lo * es;
+            ++job.npeers;
+        }
+        st = host_path(hp, job, (hi - lo) * es);
+        if (st) return st;
+        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.s_down));
+        rec->used_mask |= 1u << (a + 1);
+        HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));
     }
-    st = host_path(job, host_bytes);
-    if (st) return st;
-    HIP_TRY(hipEventRecord(rec->host_done, s_h2d));
-    HIP_TRY(hipStreamWaitEvent(stream, rec->host_done, 0));
     return FLEX_OK;
 }
 
 // MeasurePathTimings of Algorithm 1: median per-path time of cfg.tune_reps
-// calls at a fixed host share.  T[path] in seconds.
+// calls at fixed shares.  units[p], p >= 1: share of auxiliary path p.
+// T[path] in seconds.
 int flex_comm::measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
-                             hipStream_t stream, uint32_t units, double* T) {
+                             hipStream_t stream, const uint32_t* units, double* T) {
     CollState& cs = coll[c];
     cs.mode = FLEX_SPLIT_STATIC;
-    cs.static_units = units;
-    std::vector<double> td, th;
+    for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = p < npaths() ? units[p] : 0;
+    std::vector<double> t[FLEX_MAX_PATHS];
     for (uint32_t k = 0; k < cfg.tune_reps + 1; ++k) {
         const uint64_t before = cs.samples;
         int st = collective(c, bufs, out, count, dtype, stream);
@@ -545,15 +629,31 @@ int flex_comm::measure_split(int c, const void* const* bufs, void* out, size_t c
         if (st) return st;
         if (cs.samples == before)
             return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: a split call produced no timing sample");
-        if (k == 0) continue;  // first call warms the path up
-        td.push_back(cs.last_t[FLEX_PATH_DEVICE]);
-        th.push_back(cs.last_t[FLEX_PATH_HOST]);
+        if (k == 0) continue;  // first call warms the paths up
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p) t[p].push_back(cs.last_t[p]);
     }
-    std::sort(td.begin(), td.end());
-    std::sort(th.begin(), th.end());
-    const size_t n = td.size();
-    T[FLEX_PATH_DEVICE] = (n & 1) ? td[n / 2] : (td[n / 2 - 1] + td[n / 2]) / 2.0;
-    T[FLEX_PATH_HOST] = (n & 1) ? th[n / 2] : (th[n / 2 - 1] + th[n / 2]) / 2.0;
+    for (int p = 0; p < FLEX_MAX_PATHS; ++p) T[p] = median_of(t[p]);
+    return FLEX_OK;
+}
+
+// Median time of the whole message on the device path alone.
+int flex_comm::time_device_alone(int c, const void* const* bufs, void* out, size_t count, int dtype,
+                                 hipStream_t stream, double* seconds) {
+    CollState& cs = coll[c];
+    cs.mode = FLEX_SPLIT_STATIC;
+    for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = 0;
+    std::vector<double> td;
+    for (uint32_t k = 0; k < cfg.tune_reps + 1; ++k) {
+        HIP_TRY(hipEventRecord(t0, stream));
+        int st = collective(c, bufs, out, count, dtype, stream);
+        if (st) return st;
+        HIP_TRY(hipEventRecord(t1, stream));
+        HIP_TRY(hipEventSynchronize(t1));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
+        if (k > 0) td.push_back(ms * 1e-3);
+    }
+    *seconds = median_of(td);
     return FLEX_OK;
 }
 
@@ -589,6 +689,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->min_step_bytes = 256u << 10;
     cfg->tune_accept_check = 1;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
+    cfg->num_aux_paths = 1;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -615,7 +716,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     }
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
-        c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 || c.host_blocks > 65536 || c.pipeline_depth < 1 ||
+        c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
+        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -642,41 +744,17 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal, (uint32_t)cus, 0};
+    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal,
+                       (uint32_t)cus, 0};
     m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
     // host path kernels: a fixed, small number of workgroups striding over the
     // step, so that PCIe-bound waves do not crowd the device path off the CUs
     m->host_reduce_shape = {256, 1, 0, 0, (uint32_t)cus, c.host_blocks};
     m->host_copy_shape = {256, 2, 0, 0, (uint32_t)cus, c.host_blocks};
-
-    // Side streams at the default priority.
-    CREATE_TRY(hipStreamCreateWithFlags(&m->s_d2h, hipStreamNonBlocking));
-    CREATE_TRY(hipStreamCreateWithFlags(&m->s_h2d, hipStreamNonBlocking));
     CREATE_TRY(hipEventCreate(&m->t0));
     CREATE_TRY(hipEventCreate(&m->t1));
 
     if (nranks > 1) {
-        for (uint32_t s = 0; s < c.num_slots; ++s) {
-            void* p = nullptr;
-            CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes * (size_t)(nranks - 1), hipHostMallocDefault));
-            m->pinned.push_back(p);
-            hipEvent_t e = nullptr;
-            CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            m->ev_full.push_back(e);
-            e = nullptr;
-            CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            m->ev_empty.push_back(e);
-            if (c.slot_sync == FLEX_SYNC_COUNTERS) {
-                // stream memory operations need signal memory, 8 bytes per allocation
-                for (auto* vec : {&m->sem_full, &m->sem_empty}) {
-                    uint32_t* sem = nullptr;
-                    CREATE_TRY(hipExtMallocWithFlags((void**)&sem, 8, hipMallocSignalMemory));
-                    vec->push_back(sem);
-                    CREATE_TRY(hipMemset(sem, 0, 8));
-                }
-                m->slot_uses.push_back(0);
-            }
-        }
         if (c.slot_sync == FLEX_SYNC_COUNTERS) {
             int can = 0;
             CREATE_TRY(hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, m->device));
@@ -685,23 +763,55 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
                 flex_comm_destroy(m);
                 return FLEX_ERR_UNSUPPORTED;
             }
-            CREATE_TRY(hipDeviceSynchronize());
         }
-        // scratch: per peer, the largest host part a call may have (rounded up
-        // by one alignment quantum of the widest element and to 256 bytes)
+        // DMA-engine scratch: per peer, the largest part a call may route to the
+        // path (rounded up by one alignment quantum of the widest element)
         unsigned __int128 part = (unsigned __int128)max_bytes_per_rank * c.max_host_units;
         size_t per_peer = (size_t)((part + b.share_total - 1) / b.share_total);
         per_peer += (size_t)c.split_align_elems * 4 * 2;
         per_peer = std::min(per_peer, max_bytes_per_rank);
         per_peer = (per_peer + 255) / 256 * 256;
-        m->scratch_stride = per_peer;
-        if (c.host_engine == FLEX_ENGINE_SDMA && c.max_host_units > 0 && max_bytes_per_rank > 0)
-            CREATE_TRY(hipMalloc((void**)&m->scratch, per_peer * (size_t)(nranks - 1)));
+
+        m->naux = (int)c.num_aux_paths;
+        for (int a = 0; a < m->naux; ++a) {
+            HostPath& hp = m->aux[a];
+            // the first auxiliary path uses the configured engine, the second the other one
+            hp.engine = a == 0 ? (int)c.host_engine : (c.host_engine == FLEX_ENGINE_KERNEL ? FLEX_ENGINE_SDMA
+                                                                                           : FLEX_ENGINE_KERNEL);
+            // side streams at the default priority
+            CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
+            CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
+            for (uint32_t s = 0; s < c.num_slots; ++s) {
+                void* p = nullptr;
+                CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes * (size_t)(nranks - 1), hipHostMallocDefault));
+                hp.pinned.push_back(p);
+                hipEvent_t e = nullptr;
+                CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                hp.ev_full.push_back(e);
+                e = nullptr;
+                CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                hp.ev_empty.push_back(e);
+                if (c.slot_sync == FLEX_SYNC_COUNTERS) {
+                    // stream memory operations need signal memory, 8 bytes per allocation
+                    for (auto* vec : {&hp.sem_full, &hp.sem_empty}) {
+                        uint32_t* sem = nullptr;
+                        CREATE_TRY(hipExtMallocWithFlags((void**)&sem, 8, hipMallocSignalMemory));
+                        vec->push_back(sem);
+                        CREATE_TRY(hipMemset(sem, 0, 8));
+                    }
+                    hp.slot_uses.push_back(0);
+                }
+            }
+            hp.scratch_stride = per_peer;
+            if (hp.engine == FLEX_ENGINE_SDMA && c.max_host_units > 0 && max_bytes_per_rank > 0)
+                CREATE_TRY(hipMalloc((void**)&hp.scratch, per_peer * (size_t)(nranks - 1)));
+        }
+        if (c.slot_sync == FLEX_SYNC_COUNTERS) CREATE_TRY(hipDeviceSynchronize());
+
         m->ring.resize(kRingSize);
         for (auto& rec : m->ring) {
             CREATE_TRY(hipEventCreate(&rec.fork));
-            CREATE_TRY(hipEventCreate(&rec.dev_done));
-            CREATE_TRY(hipEventCreate(&rec.host_done));
+            for (int p = 0; p < 1 + m->naux; ++p) CREATE_TRY(hipEventCreate(&rec.done[p]));
         }
     }
 #undef CREATE_TRY
@@ -711,23 +821,14 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
 
 int flex_comm_destroy(flex_comm_t* m) {
     if (!m) return FLEX_OK;
-    if (m->s_d2h) (void)hipStreamSynchronize(m->s_d2h);
-    if (m->s_h2d) (void)hipStreamSynchronize(m->s_h2d);
+    for (auto& hp : m->aux) hp.destroy();
     for (auto& rec : m->ring) {
         if (rec.fork) (void)hipEventDestroy(rec.fork);
-        if (rec.dev_done) (void)hipEventDestroy(rec.dev_done);
-        if (rec.host_done) (void)hipEventDestroy(rec.host_done);
+        for (auto e : rec.done)
+            if (e) (void)hipEventDestroy(e);
     }
-    for (auto e : m->ev_full) (void)hipEventDestroy(e);
-    for (auto e : m->ev_empty) (void)hipEventDestroy(e);
-    for (auto p : m->sem_full) (void)hipFree(p);
-    for (auto p : m->sem_empty) (void)hipFree(p);
-    for (auto p : m->pinned) (void)hipHostFree(p);
-    if (m->scratch) (void)hipFree(m->scratch);
     if (m->t0) (void)hipEventDestroy(m->t0);
     if (m->t1) (void)hipEventDestroy(m->t1);
-    if (m->s_d2h) (void)hipStreamDestroy(m->s_d2h);
-    if (m->s_h2d) (void)hipStreamDestroy(m->s_h2d);
     delete m;
     return FLEX_OK;
 }
@@ -753,18 +854,36 @@ int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void
     return comm->allgather(rank_slices, out, slice_count, dtype, (hipStream_t)hip_stream);
 }
 
-int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
-    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: comm is NULL");
+int flex_set_split_paths(flex_comm_t* comm, int coll, int mode, const uint32_t* aux_units, int naux) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: comm is NULL");
     if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
-        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown collective %d", coll);
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: unknown collective %d", coll);
     if (mode != FLEX_SPLIT_STATIC && mode != FLEX_SPLIT_ADAPTIVE)
-        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: unknown mode %d", mode);
-    if (mode == FLEX_SPLIT_STATIC && host_units > comm->cfg.max_host_units)
-        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split: host share %u exceeds max_host_units %u",
-                          host_units, comm->cfg.max_host_units);
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: unknown mode %d", mode);
+    if (mode == FLEX_SPLIT_STATIC) {
+        if (naux < 0 || naux > kMaxAux || (naux > 0 && !aux_units))
+            return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: bad share array");
+        uint64_t sum = 0;
+        for (int a = 0; a < naux; ++a) {
+            if (aux_units[a] > comm->cfg.max_host_units)
+                return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: share %u exceeds max_host_units %u",
+                                  aux_units[a], comm->cfg.max_host_units);
+            if (aux_units[a] > 0 && a >= std::max(comm->naux, 1))
+                return flex::fail(FLEX_ERR_INVALID_ARG,
+                                  "flex_set_split_paths: the communicator has %d auxiliary path(s)", comm->naux);
+            sum += aux_units[a];
+        }
+        if (sum > comm->cfg.balancer.share_total)
+            return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: shares exceed share_total");
+        CollState& cs = comm->coll[coll];
+        for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = p - 1 < naux ? aux_units[p - 1] : 0;
+    }
     comm->coll[coll].mode = (uint32_t)mode;
-    if (mode == FLEX_SPLIT_STATIC) comm->coll[coll].static_units = host_units;
     return FLEX_OK;
+}
+
+int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
+    return flex_set_split_paths(comm, coll, mode, &host_units, 1);
 }
 
 int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
@@ -777,96 +896,86 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     if (count == 0) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: empty message");
     hipStream_t stream = (hipStream_t)hip_stream;
     CollState& cs = comm->coll[coll];
-    const uint32_t saved_mode = cs.mode, saved_units = cs.static_units;
     const size_t es = flex::dtype_size(dtype);
     const double msg_bytes = (double)count * es;
-    const flex_balancer_cfg_t& bc = comm->cfg.balancer;
+    const flex_config_t& cfg = comm->cfg;
+    const flex_balancer_cfg_t& bc = cfg.balancer;
+    const int np = std::max(comm->npaths(), 2);  // a communicator without peers still reports two paths
     flex_tune_result_t res;
     memset(&res, 0, sizeof res);
 
     struct Restore {
         CollState& cs;
-        uint32_t mode, units;
+        uint32_t mode;
+        uint32_t units[FLEX_MAX_PATHS];
         ~Restore() {
             cs.mode = mode;
-            cs.static_units = units;
+            memcpy(cs.static_units, units, sizeof units);
         }
-    } restore{cs, saved_mode, saved_units};
+    } restore{cs, cs.mode, {cs.static_units[0], cs.static_units[1], cs.static_units[2], cs.static_units[3]}};
 
     st = comm->poll(true);
     if (st) return st;
 
     // Rate of the device path carrying the whole message alone.
-    cs.mode = FLEX_SPLIT_STATIC;
-    cs.static_units = 0;
-    std::vector<double> td;
-    for (uint32_t k = 0; k < comm->cfg.tune_reps + 1; ++k) {
-        HIP_TRY(hipEventRecord(comm->t0, stream));
-        st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
-        if (st) return st;
-        HIP_TRY(hipEventRecord(comm->t1, stream));
-        HIP_TRY(hipEventSynchronize(comm->t1));
-        float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, comm->t0, comm->t1));
-        if (k > 0) td.push_back(ms * 1e-3);
-    }
-    std::sort(td.begin(), td.end());
-    const double t_dev_alone = td[td.size() / 2];
+    double t_dev_alone = 0;
+    st = comm->time_device_alone(coll, rank_bufs, out, count, dtype, stream, &t_dev_alone);
+    if (st) return st;
     res.path_bw[FLEX_PATH_DEVICE] = t_dev_alone > 0 ? msg_bytes / t_dev_alone : 0.0;
 
-    // Rate of the host path, measured on a probe share of the message.
+    // Rate of each host path, measured on a probe share of the message with the
+    // other host path idle.
     double T[FLEX_MAX_PATHS] = {0, 0, 0, 0};
-    uint32_t probe = std::min(comm->cfg.probe_units, comm->cfg.max_host_units);
-    uint64_t split = count;
-    if (comm->nranks > 1 && probe > 0)
-        split = flex::partition(count, probe, bc.share_total, comm->cfg.split_align_elems,
-                                comm->cfg.min_split_bytes / es);
-    if (split < count) {
-        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, probe, T);
+    const uint32_t probe = std::min(cfg.probe_units, cfg.max_host_units);
+    for (int p = 1; p < comm->npaths() && probe > 0; ++p) {
+        uint32_t units[FLEX_MAX_PATHS] = {0, 0, 0, 0};
+        units[p] = probe;
+        uint64_t start[FLEX_MAX_PATHS + 1];
+        flex::partition_paths(count, units, comm->npaths(), bc.share_total, cfg.split_align_elems,
+                              cfg.min_split_bytes / es, start);
+        const uint64_t part = start[p + 1] - start[p];
+        if (part == 0) continue;
+        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, T);
         if (st) return st;
-        res.path_bw[FLEX_PATH_HOST] = T[FLEX_PATH_HOST] > 0 ? (double)(count - split) * es / T[FLEX_PATH_HOST] : 0.0;
+        res.path_bw[p] = T[p] > 0 ? (double)part * es / T[p] : 0.0;
     }
 
     SizeClass sc;
     sc.tuned = true;
-    if (!(res.path_bw[FLEX_PATH_DEVICE] > 0) ||
-        !sc.bal.init_from_bandwidth(2, res.path_bw, bc))
+    if (!(res.path_bw[FLEX_PATH_DEVICE] > 0) || !sc.bal.init_from_bandwidth(np, res.path_bw, bc))
         return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: could not measure the device path");
-    for (int p = 0; p < 2; ++p) res.initial_shares[p] = sc.bal.shares[p];
+    for (int p = 0; p < np; ++p) res.initial_shares[p] = sc.bal.shares[p];
+
+    auto clamped = [&](uint32_t* units) {
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p)
+            units[p] = p >= 1 && p < np ? std::min(sc.bal.shares[p], cfg.max_host_units) : 0;
+    };
 
     // Algorithm 1 with real measurements.
     while (sc.bal.stage == FLEX_STAGE_TUNING) {
-        uint32_t units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+        uint32_t units[FLEX_MAX_PATHS];
+        clamped(units);
         st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, T);
         if (st) return st;
         if (!sc.bal.update(T))
-            return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: unusable path timings (%g s, %g s)", T[0], T[1]);
+            return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: unusable path timings (%g s, %g s, %g s)", T[0],
+                              T[1], T[2]);
     }
-    for (int p = 0; p < 2; ++p) res.balanced_shares[p] = sc.bal.shares[p];
+    for (int p = 0; p < np; ++p) res.balanced_shares[p] = sc.bal.shares[p];
     res.device_alone_s = t_dev_alone;
 
     // Acceptance check: the balanced split must beat the device path alone.
-    if (comm->cfg.tune_accept_check && (sc.bal.active_mask & (1u << FLEX_PATH_HOST))) {
-        uint32_t units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+    if (cfg.tune_accept_check && (sc.bal.active_mask & ~1u)) {
+        uint32_t units[FLEX_MAX_PATHS];
+        clamped(units);
         double Tc[FLEX_MAX_PATHS] = {0, 0, 0, 0};
         st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, Tc);
         if (st) return st;
-        res.combined_s = std::max(Tc[FLEX_PATH_DEVICE], Tc[FLEX_PATH_HOST]);
+        for (int p = 0; p < np; ++p)
+            if (sc.bal.active_mask & (1u << p)) res.combined_s = std::max(res.combined_s, Tc[p]);
         // device path alone again, right next to it
-        cs.static_units = 0;
-        std::vector<double> again;
-        for (uint32_t k = 0; k < comm->cfg.tune_reps + 1; ++k) {
-            HIP_TRY(hipEventRecord(comm->t0, stream));
-            st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
-            if (st) return st;
-            HIP_TRY(hipEventRecord(comm->t1, stream));
-            HIP_TRY(hipEventSynchronize(comm->t1));
-            float ms = 0.f;
-            HIP_TRY(hipEventElapsedTime(&ms, comm->t0, comm->t1));
-            if (k > 0) again.push_back(ms * 1e-3);
-        }
-        std::sort(again.begin(), again.end());
-        res.device_alone_s = again[again.size() / 2];
+        st = comm->time_device_alone(coll, rank_bufs, out, count, dtype, stream, &res.device_alone_s);
+        if (st) return st;
         if (!(res.combined_s < res.device_alone_s)) {
             sc.bal.revert_to_primary();
             res.reverted = 1;
@@ -874,14 +983,19 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     }
 
     // leave `out` holding a result computed after the last share change
-    cs.static_units = std::min(sc.bal.shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+    {
+        uint32_t units[FLEX_MAX_PATHS];
+        clamped(units);
+        memcpy(cs.static_units, units, sizeof units);
+        cs.mode = FLEX_SPLIT_STATIC;
+    }
     st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
     if (st) return st;
     HIP_TRY(hipStreamSynchronize(stream));
     st = comm->poll(true);
     if (st) return st;
 
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < np; ++p) {
         res.shares[p] = sc.bal.shares[p];
         res.path_time_s[p] = T[p];
     }
@@ -901,12 +1015,14 @@ int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, c
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: unknown collective %d", coll);
     const size_t es = flex::dtype_size(dtype);
     if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_set_shares: unknown dtype %d", dtype);
-    if (shares[FLEX_PATH_HOST] > comm->cfg.max_host_units)
-        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: host share %u exceeds max_host_units %u",
-                          shares[FLEX_PATH_HOST], comm->cfg.max_host_units);
+    const int np = std::max(comm->npaths(), 2);
+    for (int p = 1; p < np; ++p)
+        if (shares[p] > comm->cfg.max_host_units)
+            return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: share %u exceeds max_host_units %u",
+                              shares[p], comm->cfg.max_host_units);
     SizeClass sc;
     sc.tuned = true;
-    if (!sc.bal.init_from_shares(2, shares, comm->cfg.balancer))
+    if (!sc.bal.init_from_shares(np, shares, comm->cfg.balancer))
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: shares must sum to share_total");
     sc.bal.finish_tuning();
     auto& slot = comm->coll[coll].classes[size_class_of(count * es)];
@@ -939,12 +1055,15 @@ int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_st
     out->samples = cs.samples;
     out->blocking_reads = comm->blocking_reads;
     out->last_count = cs.last_count;
-    out->last_split = cs.last_split;
+    out->last_split = cs.last_start[1];
     out->mode = cs.mode;
-    out->static_host_units = cs.static_units;
+    out->static_host_units = cs.static_units[1];
+    out->npaths = (uint32_t)comm->npaths();
     for (int p = 0; p < FLEX_MAX_PATHS; ++p) {
         out->last_time_s[p] = cs.last_t[p];
         out->mean_time_s[p] = cs.samples ? cs.sum_t[p] / (double)cs.samples : 0.0;
+        out->static_units[p] = cs.static_units[p];
+        out->last_start[p] = cs.last_start[p];
     }
     if (SizeClass* sc = comm->find_class(coll, size_class_of(count * es))) sc->bal.get(&out->balancer);
     return FLEX_OK;

@@ -26,6 +26,30 @@ inline uint64_t partition(uint64_t count, uint32_t host_units, uint32_t share_to
     return split;
 }
 
+// The same cut for several auxiliary paths.  Path p carries elements
+// [start[p], start[p+1]); start[0] = 0 and start[npaths] = count.  The last
+// path takes the end of the message, the one before it the piece in front of
+// that, and so on; what is left at the front is the primary path's.  Each
+// auxiliary path p >= 1 is owed floor(count * units[p] / share_total) elements,
+// its start is rounded down to a multiple of `align` (never below 0), and a
+// non-zero share never yields an empty piece.  units[0] is ignored.
+inline void partition_paths(uint64_t count, const uint32_t* units, int npaths, uint32_t share_total,
+                            uint32_t align, uint64_t min_count, uint64_t* start) {
+    uint64_t end = count;
+    start[npaths] = count;
+    for (int p = npaths - 1; p >= 1; --p) {
+        uint64_t s = end;
+        if (units[p] > 0 && count >= min_count && count >= align) {
+            uint64_t owed = (uint64_t)(((unsigned __int128)count * units[p]) / share_total);
+            s = end > owed ? ((end - owed) / align) * align : 0;
+            if (s == end) s = end >= align ? ((end - 1) / align) * align : 0;
+        }
+        start[p] = s;
+        end = s;
+    }
+    start[0] = 0;
+}
+
 // Algorithm 1 as a state machine plus the Stage-2 window logic.
 struct Balancer {
     struct Sample {

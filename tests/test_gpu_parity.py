@@ -355,6 +355,87 @@ def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
         assert st.last_time_s[0] > 0 and st.last_time_s[1] > 0
 
 
+# ------------------------------------------------------------ three paths
+
+@pytest.mark.parametrize("first_engine", ENGINES)
+@pytest.mark.parametrize("sync", [fx.FLEX_SYNC_EVENTS, fx.FLEX_SYNC_COUNTERS])
+def test_three_paths_give_the_same_bits(first_engine, sync):
+    # device path + two host-staged paths (copy kernels and DMA engines) at once
+    count = (1 << 21) + 2048 * 3 + 5
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    host = [wl.to_numpy_bits(b) for b in bufs]
+    want_ar, want_ag = oc.allreduce(host), oc.allgather(host)
+    rs_bufs = [b[:8 * (count // 8)] for b in bufs]
+    for rank in (0, 6):
+        with Comm(rank=rank, max_host_units=10000, num_aux_paths=2, host_engine=first_engine, slot_sync=sync,
+                  chunk_bytes=256 << 10, min_step_bytes=32 << 10) as comm:
+            for shares in ((300, 500), (0, 700), (700, 0), (1, 1), (2500, 2500), (5000, 5000), (0, 10000)):
+                say("three paths", first_engine, sync, rank, shares)
+                for coll in (fx.FLEX_ALLREDUCE, fx.FLEX_ALLGATHER, fx.FLEX_REDUCESCATTER):
+                    fx.flex_set_split_paths(comm, coll, fx.FLEX_SPLIT_STATIC, shares)
+                out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+                fx.flex_allreduce_local(comm, bufs, out)
+                out_ag = torch.zeros(8 * count, dtype=torch.bfloat16, device=DEV)
+                fx.flex_allgather_local(comm, bufs, out_ag)
+                out_rs = torch.zeros(count // 8, dtype=torch.bfloat16, device=DEV)
+                fx.flex_reducescatter_local(comm, rs_bufs, out_rs)
+                torch.cuda.synchronize()
+                assert_same_bits(out, want_ar, "allreduce %s" % (shares,))
+                assert wl.to_numpy_bits(out_ag).tobytes() == want_ag.tobytes(), shares
+                assert_same_bits(out_rs, oc.reducescatter([wl.to_numpy_bits(b) for b in rs_bufs], rank),
+                                 "reducescatter %s" % (shares,))
+                st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+                assert st.npaths == 3
+                assert list(st.last_start)[:3] == fx.flex_partition_paths(count, [0, *shares], 10000, 2048, 32768)[:3]
+            fx.flex_evaluator_drain(comm)
+            st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+            assert st.samples == st.split_calls == 7
+            with pytest.raises(fx.FlexError):
+                fx.flex_set_split_paths(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, (6000, 6000))
+    with Comm() as comm:       # one host path only: a share for a second one is refused
+        with pytest.raises(fx.FlexError):
+            fx.flex_set_split_paths(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, (100, 100))
+
+
+def test_three_path_balancer_on_hardware():
+    # Algorithm 1 with three real paths, then Stage 2 from installed shares
+    count = 64 * wl.MIB        # 128 MiB per rank
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want = oracle_allreduce(bufs)
+    with Comm(max_bytes=count * 2, num_aux_paths=2) as comm:
+        out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+        res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
+        say("tune3", res.as_dict())
+        torch.cuda.synchronize()
+        assert_same_bits(out, want, "after tune")
+        assert sum(res.shares) == 10000 and sum(res.initial_shares) == 10000 and res.iterations <= 100
+        assert res.path_bw[0] > 0 and res.path_bw[1] > 0 and res.path_bw[2] > 0
+        denom = res.path_bw[0] + res.path_bw[1] + res.path_bw[2]
+        assert res.initial_shares[1] == int(10000 * res.path_bw[1] / denom)
+        assert res.initial_shares[2] == int(10000 * res.path_bw[2] / denom)
+        if res.reverted:
+            assert list(res.shares)[:3] == [10000, 0, 0]
+        # Stage 2 on three live paths
+        fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9880, 60, 60])
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
+        before = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16).samples
+        traj = [[9880, 60, 60]]
+        for k in range(60):
+            fx.flex_allreduce_local(comm, bufs, out)
+            if k % 10 == 9:
+                torch.cuda.synchronize()
+                assert_same_bits(out, want, "adaptive call %d" % k)
+                fx.flex_evaluator_drain(comm)
+                st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+                traj.append(list(st.balancer.shares)[:3])
+        say("stage2 on three paths", traj, st.as_dict())
+        for a, b in zip(traj, traj[1:]):
+            assert sum(b) == 10000
+            moved = [y - x for x, y in zip(a, b)]
+            assert sorted(moved) in ([0, 0, 0], [-4, 0, 4])      # one fixed step from one path to another
+        assert st.samples - before == 60 and st.last_time_s[2] > 0
+
+
 # --------------------------------------------------------- full-size configs
 
 def test_config0_allreduce_f32_1MiB():

@@ -35,7 +35,7 @@ def test_struct_layout_defaults_come_through():
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
     assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 16, 4, 256 << 10)
-    assert c.tune_accept_check == 1 and c.slot_sync == 0
+    assert c.tune_accept_check == 1 and c.slot_sync == 0 and c.num_aux_paths == 1
     b = c.balancer
     assert (b.share_total, b.initial_step, b.stability_required, b.max_tune_iters, b.window,
             b.runtime_step) == (10000, 64, 3, 100, 10, 4)
@@ -202,3 +202,20 @@ def test_library_revert_to_primary():
     for _ in range(25):      # drained paths never come back
         assert fx.flex_balancer_update(b, [5.0, 0.0, 0.0]) == [10000, 0, 0]
     fx.flex_balancer_destroy(b)
+
+
+@given(count=st.integers(0, 1 << 36), units=st.lists(st.integers(0, 3333), min_size=1, max_size=3),
+       align=st.sampled_from([1, 64, 2048]), min_count=st.sampled_from([0, 32768, 1 << 20]))
+@settings(max_examples=500, deadline=None)
+def test_library_partition_paths_equals_oracle(count, units, align, min_count):
+    u = [0] + units
+    assert fx.flex_partition_paths(count, u, 10000, align, min_count) == op.partition_paths(count, u, 10000, align, min_count)
+    if len(u) == 2:
+        assert fx.flex_partition_paths(count, u, 10000, align, min_count)[1] == fx.flex_partition(count, u[1], 10000, align, min_count)
+
+
+def test_library_partition_paths_rejects_bad_input():
+    with pytest.raises(fx.FlexError):
+        fx.flex_partition_paths(100, [0, 6000, 6000])
+    with pytest.raises(fx.FlexError):
+        fx.flex_partition_paths(100, [0, 1, 1, 1, 1])

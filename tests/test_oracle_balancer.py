@@ -256,3 +256,42 @@ def test_partition_properties(count, units):
     owed = count * units // 10000
     assert host >= owed and host > 0
     assert host - owed <= 2048 + 2048          # rounding adds less than two quanta
+
+
+def test_partition_paths_reduces_to_the_two_path_cut():
+    for count in (0, 5, 40000, 1 << 20, 1000003, (1 << 27) + 17):
+        for u in (0, 1, 37, 500, 2200, 9999, 10000):
+            assert op.partition_paths(count, [0, u]) == [0, op.partition(count, u), count]
+
+
+def test_partition_paths_hand_values():
+    # 2^20 elements, 5 % and 12 %: owed 52428 and 125829.  The last path's piece
+    # starts at floor((1048576 - 125829) / 2048) * 2048 = 921600; the middle one
+    # at floor((921600 - 52428) / 2048) * 2048 = 868352.
+    assert op.partition_paths(1 << 20, [0, 500, 1200]) == [0, 868352, 921600, 1 << 20]
+    # a path with share 0 gets nothing; everything to the last path
+    assert op.partition_paths(1 << 20, [0, 0, 10000]) == [0, 0, 0, 1 << 20]
+    assert op.partition_paths(1 << 20, [0, 10000, 0]) == [0, 0, 1 << 20, 1 << 20]
+    # tiny shares still get one quantum each
+    assert op.partition_paths(1 << 20, [0, 1, 1]) == [0, (1 << 20) - 4096, (1 << 20) - 2048, 1 << 20]
+    assert op.partition_paths(1000, [0, 5000, 5000]) == [0, 1000, 1000, 1000]      # too short to split
+
+
+@given(count=st.integers(0, 1 << 34), u1=st.integers(0, 5000), u2=st.integers(0, 5000), u3=st.integers(0, 0))
+@settings(max_examples=500, deadline=None)
+def test_partition_paths_properties(count, u1, u2, u3):
+    start = op.partition_paths(count, [0, u1, u2])
+    assert start[0] == 0 and start[3] == count and start == sorted(start)
+    if count < 32768:
+        assert start[1] == start[2] == count
+        return
+    for p, u in ((1, u1), (2, u2)):
+        piece = start[p + 1] - start[p]
+        owed = count * u // 10000
+        if u == 0:
+            assert piece == 0
+        else:
+            assert piece > 0 or start[p + 1] == 0
+            assert start[p] % 2048 == 0
+            if start[p] > 0:
+                assert owed <= piece < owed + 2 * 2048
