@@ -418,6 +418,12 @@ int flex_evaluator_drain(flex_comm_t* comm);
  * `count` elements of `dtype`.  out: host pointer. */
 int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out);
 
+/* sizeof() of the structs of this header as the library was compiled, for
+ * bindings that mirror them: out[0..4] = flex_balancer_cfg_t,
+ * flex_balancer_state_t, flex_config_t, flex_stats_t, flex_tune_result_t.
+ * out: host array of 5.  Errors: INVALID_ARG (null). */
+int flex_struct_sizes(size_t* out);
+
 /* Static strings; never NULL. */
 const char* flex_status_string(int status);
 const char* flex_last_error(void);

@@ -115,6 +115,7 @@ def lib():
         "flex_partition": [u64, u32, u32, u32, u64, P(u64)],
         "flex_partition_paths": [u64, P(u32), ci, u32, u32, u64, P(u64)],
         "flex_set_split_paths": [vp, ci, ci, P(u32), ci],
+        "flex_struct_sizes": [P(sz)],
         "flex_config_default": [P(Config)],
         "flex_comm_create": [pvp, ci, ci, sz, P(Config)],
         "flex_comm_destroy": [vp],
@@ -203,6 +204,12 @@ def flex_balancer_get(b):
 
 def flex_balancer_destroy(b):
     _check(lib().flex_balancer_destroy(b))
+
+
+def flex_struct_sizes():
+    out = (ctypes.c_size_t * 5)()
+    _check(lib().flex_struct_sizes(out))
+    return list(out)
 
 
 def flex_partition(count, host_units, share_total=10000, align_elems=2048, min_count=32768):

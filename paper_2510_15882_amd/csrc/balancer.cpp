@@ -275,6 +275,16 @@ int flex_balancer_destroy(flex_balancer_t* b) {
     return FLEX_OK;
 }
 
+int flex_struct_sizes(size_t* out) {
+    if (!out) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_struct_sizes: out is NULL");
+    out[0] = sizeof(flex_balancer_cfg_t);
+    out[1] = sizeof(flex_balancer_state_t);
+    out[2] = sizeof(flex_config_t);
+    out[3] = sizeof(flex_stats_t);
+    out[4] = sizeof(flex_tune_result_t);
+    return FLEX_OK;
+}
+
 int flex_partition(uint64_t count, uint32_t host_units, uint32_t share_total, uint32_t align_elems,
                    uint64_t min_count, uint64_t* split_out) {
     if (!split_out || share_total == 0 || align_elems == 0 || host_units > share_total)

@@ -219,3 +219,17 @@ def test_library_partition_paths_rejects_bad_input():
         fx.flex_partition_paths(100, [0, 6000, 6000])
     with pytest.raises(fx.FlexError):
         fx.flex_partition_paths(100, [0, 1, 1, 1, 1])
+
+
+def test_binding_structs_have_the_library_layout():
+    import ctypes
+    want = [ctypes.sizeof(t) for t in (fx.BalancerCfg, fx.BalancerState, fx.Config, fx.Stats, fx.TuneResult)]
+    assert fx.flex_struct_sizes() == want
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    from paper_2510_15882_amd import build
+    monkeypatch.setattr(fx, "_lib", None)
+    monkeypatch.setattr(build, "LIB", str(tmp_path / "libflexlink.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        fx.flex_config_default()
