@@ -12,8 +12,8 @@ Successive steps rotate over --buffer-sets independent sets of input and output
 buffers (default 3, about 8 GiB in all), so that every byte a step touches was
 last touched several GiB of traffic earlier: the 256 MB Infinity Cache cannot
 keep an output buffer resident from one call to the next and the HBM traffic
-equals the algorithmic bytes.  The same-buffers-every-call figure (what
-nccl-tests style loops measure) is reported under extras.warm_same_buffers.
+equals the algorithmic bytes.  The same-buffers-every-call figures (what
+nccl-tests style loops measure) are reported under extras.warm_same_buffers*.
 
 Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
 timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
@@ -288,8 +288,25 @@ def main():
             d_ag = median(timed_calls(ag, 60, rotate))
             extras[name] = {"allreduce_ms": d_ar, "allreduce_hbm_GBs": ar_bytes / d_ar / 1e6,
                             "allgather_ms": d_ag, "allgather_hbm_GBs": ag_bytes / d_ag / 1e6}
-        extras["warm_same_buffers"]["note"] = ("the 256 MiB output stays resident in the 256 MB Infinity Cache "
-                                               "between calls: HBM sees fewer bytes than the algorithm moves")
+        extras["warm_same_buffers"]["note"] = ("same buffers every call, library defaults (non-temporal stores "
+                                               "do not linger in the Infinity Cache, so this is close to cold)")
+        # plain (write-back) stores let a reused 256 MiB output stay resident in the 256 MB Infinity Cache:
+        # HBM then sees fewer bytes than the algorithm moves
+        cfg2 = fx.flex_config_default()
+        cfg2.reduce_nontemporal = 1
+        comm2 = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg2)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(60)]
+        with torch.cuda.stream(stream):
+            for a, b in evs:
+                a.record(stream)
+                fx.flex_allreduce_local(comm2, sets[0][0], sets[0][1], stream=stream)
+                b.record(stream)
+        stream.synchronize()
+        fx.flex_comm_destroy(comm2)
+        d = median([a.elapsed_time(b) for a, b in evs])
+        extras["warm_same_buffers_plain_stores"] = {
+            "allreduce_ms": d, "allreduce_hbm_GBs": ar_bytes / d / 1e6,
+            "note": "reduce_nontemporal = 1: the reused output stays in the Infinity Cache, its stores never reach HBM"}
         # configuration 2's static split sweep: device-only vs 5 / 12 / 22 % through pinned host memory
         sweep = {}
         for units in (0, 100, 500, 1200, 2200):
