@@ -68,7 +68,7 @@ enum flex_status {
 
 enum flex_dtype { FLEX_F32 = 0, FLEX_BF16 = 1, FLEX_F16 = 2 };
 enum flex_op { FLEX_SUM = 0 };
-enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1, FLEX_REDUCESCATTER = 2 };
+enum flex_coll { FLEX_ALLREDUCE = 0, FLEX_ALLGATHER = 1, FLEX_REDUCESCATTER = 2, FLEX_ALLTOALL = 3 };
 enum flex_path { FLEX_PATH_DEVICE = 0, FLEX_PATH_HOST = 1, FLEX_PATH_HOST2 = 2 };
 enum flex_split_mode { FLEX_SPLIT_STATIC = 0, FLEX_SPLIT_ADAPTIVE = 1 };
 enum flex_balancer_stage { FLEX_STAGE_TUNING = 1, FLEX_STAGE_RUNTIME = 2 };
@@ -360,6 +360,20 @@ int flex_reducescatter_local(flex_comm_t* comm, const void* const* rank_bufs, vo
  * convention): it is then not copied.  Errors as for flex_allreduce_local. */
 int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
                          size_t slice_count, int dtype, void* hip_stream);
+
+/* AllToAll, local share: the primitive the paper names as its next one
+ * (Limitations and Future Work).
+ *   rank_bufs  host array of nranks device pointers; rank_bufs[r] holds rank r's
+ *              nranks * count contiguous elements, piece d (count elements at
+ *              offset d * count) being addressed to rank d.
+ *   out        device pointer to nranks * count elements.
+ * Result: out[r * count + j] = rank_bufs[r][rank * count + j], bit for bit: the
+ * local rank's receive buffer.  It is flex_allgather_local applied to the pieces
+ * addressed to the local rank (same split, engines and error behaviour; the
+ * local rank's own piece is copied by the device path).  nranks * count * size
+ * must not exceed max_bytes_per_rank. */
+int flex_alltoall_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t count, int dtype,
+                        void* hip_stream);
 
 /* Choose how later calls of collective `coll` are split.
  *   FLEX_SPLIT_STATIC    every call uses host_units (0 = device path only).

@@ -30,6 +30,8 @@ def lib():
         L.oracle_f32_bits_to_f16.restype = None
         L.oracle_allgather.argtypes = [pp, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
         L.oracle_allgather.restype = None
+        L.oracle_alltoall.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
+        L.oracle_alltoall.restype = None
         L.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
         L.oracle_bf16_to_f32.restype = ctypes.c_float
         L.oracle_f32_to_bf16.argtypes = [ctypes.c_float]
@@ -97,6 +99,18 @@ def allgather(slices):
     n = len(slices)
     out = np.empty(n * slices[0].size, dtype=slices[0].dtype)
     lib().oracle_allgather(_ptr_array(slices), n, slices[0].nbytes, out.ctypes.data)
+    return out
+
+
+def alltoall(bufs, rank):
+    """Receive buffer of rank `rank`: piece r is piece number `rank` of rank r's
+    buffer (every buffer holds N pieces of equal length)."""
+    _check_inputs(bufs)
+    n = len(bufs)
+    if bufs[0].size % n:
+        raise ValueError("buffer length must be a multiple of the number of ranks")
+    out = np.empty_like(bufs[0])
+    lib().oracle_alltoall(_ptr_array(bufs), n, rank, bufs[0].nbytes // n, out.ctypes.data)
     return out
 
 

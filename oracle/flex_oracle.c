@@ -177,6 +177,19 @@ void oracle_allgather(const void *const *in, int n, size_t slice_bytes, void *ou
     }
 }
 
+/* AllToAll, the receive buffer of rank `rank`: piece r of out is what rank r
+ * addresses to `rank`, i.e. piece number `rank` of rank r's buffer.  Pieces are
+ * piece_bytes long; bytes are moved untouched. */
+void oracle_alltoall(const void *const *in, int n, int rank, size_t piece_bytes, void *out)
+{
+    unsigned char *o = (unsigned char *)out;
+    for (int r = 0; r < n; ++r) {
+        const unsigned char *s = (const unsigned char *)in[r] + (size_t)rank * piece_bytes;
+        for (size_t j = 0; j < piece_bytes; ++j)
+            o[(size_t)r * piece_bytes + j] = s[j];
+    }
+}
+
 /* Scalar conversions exported so that the tests can pin them on their own. */
 float oracle_bf16_to_f32(uint16_t h) { return bf16_bits_to_f32(h); }
 uint16_t oracle_f32_to_bf16(float f) { return f32_to_bf16_bits(f); }

@@ -17,7 +17,7 @@ FLEX_MAX_PATHS = 4
 FLEX_OK, FLEX_ERR_INVALID_ARG, FLEX_ERR_UNSUPPORTED, FLEX_ERR_HIP, FLEX_ERR_NOMEM, FLEX_ERR_STATE = range(6)
 FLEX_F32, FLEX_BF16, FLEX_F16 = 0, 1, 2
 FLEX_SUM = 0
-FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER = 0, 1, 2
+FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER, FLEX_ALLTOALL = 0, 1, 2, 3
 FLEX_PATH_DEVICE, FLEX_PATH_HOST, FLEX_PATH_HOST2 = 0, 1, 2
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
@@ -122,6 +122,7 @@ def lib():
         "flex_allreduce_local": [vp, pvp, vp, sz, ci, ci, vp],
         "flex_allgather_local": [vp, pvp, vp, sz, ci, vp],
         "flex_reducescatter_local": [vp, pvp, vp, sz, ci, ci, vp],
+        "flex_alltoall_local": [vp, pvp, vp, sz, ci, vp],
         "flex_set_split": [vp, ci, ci, u32],
         "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
         "flex_comm_set_shares": [vp, ci, sz, ci, P(u32)],
@@ -290,6 +291,14 @@ def flex_allgather_local(comm, rank_slices, out, slice_count=None, stream=None):
     slice_count = rank_slices[0].numel() if slice_count is None else slice_count
     _check(lib().flex_allgather_local(comm, _pointer_array(rank_slices), out.data_ptr(), slice_count,
                                       dtype_code(out.dtype), _stream_handle(stream)))
+
+
+def flex_alltoall_local(comm, rank_bufs, out, count=None, stream=None):
+    """rank_bufs: list of nranks device tensors of nranks * count elements."""
+    _check_tensors(rank_bufs, out)
+    count = rank_bufs[0].numel() // len(rank_bufs) if count is None else count
+    _check(lib().flex_alltoall_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
+                                     dtype_code(out.dtype), _stream_handle(stream)))
 
 
 def flex_set_split(comm, coll, mode, host_units=0):

@@ -158,7 +158,7 @@ struct flex_comm {
     uint64_t blocking_reads = 0;
     hipEvent_t t0 = nullptr, t1 = nullptr;  // device-only timing in flex_comm_tune
 
-    CollState coll[3];  // indexed by flex_coll
+    CollState coll[4];  // indexed by flex_coll
 
     // ---- host-staged path --------------------------------------------------
     // Move `bytes` bytes per peer through the path's ring of pinned slots, step
@@ -430,11 +430,16 @@ struct flex_comm {
     int reduce(int c, const char* who, const void* const* bufs, void* out, size_t count, int dtype,
                hipStream_t stream);
     int reducescatter(const void* const* bufs, void* out, size_t recv_count, int dtype, hipStream_t stream);
-    int allgather(const void* const* slices, void* out, size_t count, int dtype, hipStream_t stream);
+    // AllGather, or (c == FLEX_ALLTOALL) the same gather over the pieces the
+    // peers address to the local rank
+    int gather(int c, const char* who, const void* const* slices, void* out, size_t count, int dtype,
+               hipStream_t stream);
+    int alltoall(const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream);
     int collective(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream) {
         if (c == FLEX_REDUCESCATTER) return reducescatter(bufs, out, count, dtype, stream);
+        if (c == FLEX_ALLTOALL) return alltoall(bufs, out, count, dtype, stream);
         return c == FLEX_ALLREDUCE ? reduce(c, "flex_allreduce_local", bufs, out, count, dtype, stream)
-                                   : allgather(bufs, out, count, dtype, stream);
+                                   : gather(c, "flex_allgather_local", bufs, out, count, dtype, stream);
     }
     int validate(const char* who, const void* const* bufs, const void* out, size_t count, int dtype);
     int measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
@@ -552,11 +557,29 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     return FLEX_OK;
 }
 
-int flex_comm::allgather(const void* const* slices, void* out, size_t count, int dtype,
-                         hipStream_t stream) {
-    int st = validate("flex_allgather_local", slices, out, count, dtype);
+int flex_comm::alltoall(const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream) {
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_alltoall_local: unknown dtype %d", dtype);
+    if (!bufs) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_alltoall_local: rank pointer array is NULL");
+    if (count > max_bytes / es / (size_t)nranks)
+        return flex::fail(FLEX_ERR_INVALID_ARG,
+                          "flex_alltoall_local: %d x %zu elements exceed max_bytes_per_rank %zu", nranks, count,
+                          max_bytes);
+    // what rank r sends to the local rank sits rank * count elements into r's buffer
+    const void* piece[FLEX_MAX_RANKS];
+    for (int r = 0; r < nranks; ++r) {
+        if (count > 0 && !bufs[r])
+            return flex::fail(FLEX_ERR_INVALID_ARG, "flex_alltoall_local: rank %d pointer is NULL", r);
+        piece[r] = (const char*)bufs[r] + (size_t)rank * count * es;
+    }
+    return gather(FLEX_ALLTOALL, "flex_alltoall_local", piece, out, count, dtype, stream);
+}
+
+int flex_comm::gather(int c, const char* who, const void* const* slices, void* out, size_t count, int dtype,
+                      hipStream_t stream) {
+    int st = validate(who, slices, out, count, dtype);
     if (st) return st;
-    CollState& cs = coll[FLEX_ALLGATHER];
+    CollState& cs = coll[c];
     ++cs.calls;
     if (count == 0) return FLEX_OK;
     st = poll(false);
@@ -567,7 +590,7 @@ int flex_comm::allgather(const void* const* slices, void* out, size_t count, int
     uint64_t start[FLEX_MAX_PATHS + 1];
     bool adaptive;
     SizeClass* sc;
-    const bool split = split_message(FLEX_ALLGATHER, count, es, start, &adaptive, &sc);
+    const bool split = split_message(c, count, es, start, &adaptive, &sc);
 
     const void* src[FLEX_MAX_RANKS];
     void* dst[FLEX_MAX_RANKS];
@@ -583,7 +606,7 @@ int flex_comm::allgather(const void* const* slices, void* out, size_t count, int
     }
 
     TimingRecord* rec;
-    st = begin_split_call(FLEX_ALLGATHER, slice_bytes, adaptive, sc, &rec);
+    st = begin_split_call(c, slice_bytes, adaptive, sc, &rec);
     if (st) return st;
     HIP_TRY(hipEventRecord(rec->fork, stream));
 
@@ -851,12 +874,19 @@ int flex_reducescatter_local(flex_comm_t* comm, const void* const* rank_bufs, vo
 int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
                          size_t slice_count, int dtype, void* hip_stream) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_allgather_local: comm is NULL");
-    return comm->allgather(rank_slices, out, slice_count, dtype, (hipStream_t)hip_stream);
+    return comm->gather(FLEX_ALLGATHER, "flex_allgather_local", rank_slices, out, slice_count, dtype,
+                        (hipStream_t)hip_stream);
+}
+
+int flex_alltoall_local(flex_comm_t* comm, const void* const* rank_bufs, void* out, size_t count, int dtype,
+                        void* hip_stream) {
+    if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_alltoall_local: comm is NULL");
+    return comm->alltoall(rank_bufs, out, count, dtype, (hipStream_t)hip_stream);
 }
 
 int flex_set_split_paths(flex_comm_t* comm, int coll, int mode, const uint32_t* aux_units, int naux) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: comm is NULL");
-    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: unknown collective %d", coll);
     if (mode != FLEX_SPLIT_STATIC && mode != FLEX_SPLIT_ADAPTIVE)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_set_split_paths: unknown mode %d", mode);
@@ -889,7 +919,7 @@ int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
 int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
                    int dtype, void* hip_stream, flex_tune_result_t* result) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: comm is NULL");
-    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: unknown collective %d", coll);
     int st = comm->validate("flex_comm_tune", rank_bufs, out, count, dtype);
     if (st) return st;
@@ -1011,7 +1041,7 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
 
 int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares) {
     if (!comm || !shares) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: NULL argument");
-    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: unknown collective %d", coll);
     const size_t es = flex::dtype_size(dtype);
     if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_set_shares: unknown dtype %d", dtype);
@@ -1044,7 +1074,7 @@ int flex_evaluator_drain(flex_comm_t* comm) {
 
 int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out) {
     if (!comm || !out) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: NULL argument");
-    if (coll < FLEX_ALLREDUCE || coll > FLEX_REDUCESCATTER)
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_get_stats: unknown collective %d", coll);
     const size_t es = flex::dtype_size(dtype);
     if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_get_stats: unknown dtype %d", dtype);

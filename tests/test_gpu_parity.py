@@ -249,6 +249,26 @@ def test_reducescatter_is_the_rank_slice_and_composes_to_allreduce(dtype, engine
                 assert_same_bits(full, want_full, "reduce-scatter + all-gather, rc %d" % rc)
 
 
+# --------------------------------------------------------------- AllToAll
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_alltoall_receive_buffer(dtype):
+    n = 8
+    for cnt in (0, 1, 2049, 40001, (1 << 17) + 2048):
+        bufs = [wl.random_bits(n * cnt, dtype, 60 + r, DEV) for r in range(n)]
+        host = [wl.to_numpy_bits(b) for b in bufs]
+        for rank, units, engine, paths in ((0, 0, 0, 1), (3, 1500, 0, 1), (7, 1500, 1, 1), (5, 700, 0, 2)):
+            with Comm(rank=rank, max_host_units=10000, host_engine=engine, num_aux_paths=paths,
+                      min_step_bytes=16 << 10) as comm:
+                fx.flex_set_split_paths(comm, fx.FLEX_ALLTOALL, fx.FLEX_SPLIT_STATIC, (units,) * paths)
+                out = torch.full((n * cnt + 4,), 3.0, dtype=dtype, device=DEV)
+                fx.flex_alltoall_local(comm, bufs, out, count=cnt)
+                torch.cuda.synchronize()
+                if cnt:
+                    assert wl.to_numpy_bits(out[:n * cnt]).tobytes() == oc.alltoall(host, rank).tobytes(), (cnt, rank)
+                assert torch.all(out[n * cnt:] == 3.0)
+
+
 # ------------------------------------------------- split over both paths
 
 ENGINES = [fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
@@ -653,7 +673,7 @@ def test_invalid_arguments_are_rejected_without_enqueueing():
         with pytest.raises(fx.FlexError):
             fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 2501)
         with pytest.raises(fx.FlexError):
-            fx.flex_set_split(comm, 3, fx.FLEX_SPLIT_STATIC, 0)
+            fx.flex_set_split(comm, 4, fx.FLEX_SPLIT_STATIC, 0)
         torch.cuda.synchronize()
         assert out.abs().sum() == 0          # nothing ran
         # count 0 is fine and does nothing

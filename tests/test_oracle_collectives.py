@@ -377,3 +377,16 @@ def test_reducescatter_is_the_rank_slice_of_allreduce():
         assert oc.reducescatter(bufs, rank).tobytes() == full[rank * rc:(rank + 1) * rc].tobytes()
     ints = [np.arange(n * 4, dtype=np.float32) + 100 * r for r in range(n)]
     assert oc.reducescatter(ints, 2).tolist() == [float(8 * (8 + j) + 100 * 28) for j in range(4)]
+
+
+def test_alltoall_is_a_transpose_of_pieces():
+    n, cnt = 8, 1237
+    rng = np.random.default_rng(3)
+    bufs = [rng.integers(0, 1 << 16, n * cnt, dtype=np.uint32).astype(np.uint16) for _ in range(n)]
+    cube = np.stack(bufs).reshape(n, n, cnt)                 # [sender, destination, element]
+    for rank in (0, 5, 7):
+        want = cube[:, rank, :].reshape(-1)                  # library slicing: what everybody sends to `rank`
+        assert oc.alltoall(bufs, rank).tobytes() == want.tobytes()
+    # doing it for every rank and stacking is the transpose of the first two axes
+    allrecv = np.stack([oc.alltoall(bufs, r) for r in range(n)]).reshape(n, n, cnt)
+    assert np.array_equal(allrecv, cube.transpose(1, 0, 2))
