@@ -234,7 +234,7 @@ typedef struct flex_config {
     uint32_t copy_nontemporal;   /* same for the copy kernel */
     uint32_t host_engine;        /* flex_host_engine (default FLEX_ENGINE_KERNEL) */
     uint32_t host_blocks;        /* FLEX_ENGINE_KERNEL: workgroups (of 256 threads) each host-path kernel may
-                                    occupy (default 64) */
+                                    occupy (default 16) */
     uint32_t pipeline_depth;     /* a host part shorter than pipeline_depth * chunk_bytes per peer is still
                                     cut into up to this many steps so that the two stages overlap (default 4) */
     uint32_t min_step_bytes;     /* ... but no step is shorter than this per peer (default 256 KiB) */
@@ -243,7 +243,10 @@ typedef struct flex_config {
     uint32_t slot_sync;          /* flex_slot_sync (default FLEX_SYNC_EVENTS) */
     uint32_t num_aux_paths;      /* host-staged paths: 1 (default) = FLEX_PATH_HOST with host_engine;
                                     2 = also FLEX_PATH_HOST2 with the other engine */
-    uint32_t reserved;
+    uint32_t host_die_shift;     /* FLEX_ENGINE_KERNEL: 0 = host-path workgroups spread over all 8 accelerator
+                                    dies; 1..3 = their grids are 2^shift times larger and only every 2^shift-th
+                                    workgroup works, which keeps them on 4, 2 (default) or 1 of the dies and
+                                    disturbs the device path less */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

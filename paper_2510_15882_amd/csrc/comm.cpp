@@ -713,6 +713,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->tune_accept_check = 1;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
     cfg->num_aux_paths = 1;
+    cfg->host_die_shift = 2;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -740,7 +741,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
+        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -772,8 +773,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
     // host path kernels: a fixed, small number of workgroups striding over the
     // step, so that PCIe-bound waves do not crowd the device path off the CUs
-    m->host_reduce_shape = {256, 1, 0, 0, (uint32_t)cus, c.host_blocks};
-    m->host_copy_shape = {256, 2, 0, 0, (uint32_t)cus, c.host_blocks};
+    m->host_reduce_shape = {256, 1, 0, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    m->host_copy_shape = {256, 2, 0, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
     CREATE_TRY(hipEventCreate(&m->t0));
     CREATE_TRY(hipEventCreate(&m->t1));
 

@@ -90,6 +90,9 @@ struct LaunchShape {
     uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device
     uint32_t max_blocks;    // 0 = no limit; else the grid never exceeds this many workgroups
+    // The grid is made 2^block_shift times larger and only every 2^block_shift-th
+    // workgroup works: 3 keeps the working workgroups on one of the 8 dies.
+    uint32_t block_shift = 0;
 };
 
 // Enqueue out[i] = sum over r (rank order) of in[r][i], i in [0, count), on

@@ -18,6 +18,7 @@ struct CopyArgs {
     const void* src[FLEX_MAX_RANKS];
     void* dst[FLEX_MAX_RANKS];
     uint64_t bytes[FLEX_MAX_RANKS];
+    uint32_t shift;  // only workgroups whose x index is a multiple of 2^shift work
 };
 
 template <bool NT>
@@ -38,9 +39,9 @@ __device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
 // modulo sizeof(G): byte-wise head until both are G-aligned, G-wise body,
 // byte-wise tail.  All workgroups of the slice stride over it together.
 template <typename G>
-__device__ void copy_granules(const char* s, char* d, uint64_t bytes) {
-    const uint64_t gtid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const uint64_t gsize = (uint64_t)gridDim.x * blockDim.x;
+__device__ void copy_granules(const char* s, char* d, uint64_t bytes, uint32_t bid, uint32_t nblk) {
+    const uint64_t gtid = (uint64_t)bid * blockDim.x + threadIdx.x;
+    const uint64_t gsize = (uint64_t)nblk * blockDim.x;
     uint64_t head = (sizeof(G) - ((uintptr_t)s & (sizeof(G) - 1))) & (sizeof(G) - 1);
     if (head > bytes) head = bytes;
     const uint64_t nbody = (bytes - head) / sizeof(G);
@@ -62,16 +63,22 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     char* d = (char*)a.dst[r];
     const uint64_t bytes = a.bytes[r];
     if (s == d || bytes == 0) return;  // slice already in place
+    // Workgroups go to the 8 accelerator dies round-robin by linear index, and
+    // gridDim.x is a multiple of 2^shift: with shift 3 the working ones all sit
+    // on one die.
+    if (blockIdx.x & ((1u << a.shift) - 1u)) return;
+    const uint32_t bid = blockIdx.x >> a.shift;
+    const uint32_t nblk = gridDim.x >> a.shift;
 
     const uintptr_t diff = (uintptr_t)s ^ (uintptr_t)d;
     if (diff & 15) {
         // source and destination disagree within a 16-byte line
         if ((diff & 3) == 0)
-            copy_granules<uint32_t>(s, d, bytes);
+            copy_granules<uint32_t>(s, d, bytes, bid, nblk);
         else if ((diff & 1) == 0)
-            copy_granules<uint16_t>(s, d, bytes);
+            copy_granules<uint16_t>(s, d, bytes, bid, nblk);
         else
-            copy_granules<uint8_t>(s, d, bytes);
+            copy_granules<uint8_t>(s, d, bytes, bid, nblk);
         return;
     }
 
@@ -85,7 +92,7 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
     const uint64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
 
-    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    for (uint64_t tile = bid; tile < ntiles; tile += nblk) {
         const uint64_t first = tile * tile_vecs;
         if (first + tile_vecs <= nvec) {
             u32x4 v[UNROLL];
@@ -104,7 +111,7 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     // bytes outside the aligned body (at most 15 on each side)
     const uint64_t body_end = head + nvec * 16;
     const uint64_t nloose = head + (bytes - body_end);
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
         for (uint64_t k = tid; k < nloose; k += nthreads) {
             const uint64_t i = k < head ? k : body_end + (k - head);
             d[i] = s[i];
@@ -155,7 +162,9 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
         if (gx > per_slice) gx = per_slice;
     }
     if (gx == 0) gx = 1;
-    if (gx > 0x7fffffffull) gx = 0x7fffffffull;
+    a.shift = shape.block_shift > 8 ? 8 : shape.block_shift;
+    if (gx > (0x7fffffffull >> a.shift)) gx = 0x7fffffffull >> a.shift;
+    gx <<= a.shift;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;
     switch (unroll) {

@@ -24,6 +24,7 @@ struct ReduceArgs {
     uint64_t head;   // leading elements handled one by one (until 16-byte alignment)
     uint64_t nvec;   // 16-byte vectors in the aligned body
     uint64_t count;  // all elements
+    uint32_t shift;  // only workgroups whose index is a multiple of 2^shift work
 };
 
 template <bool NT>
@@ -128,6 +129,11 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     constexpr uint32_t kVecElems = 16 / kElemSize;
     const uint32_t tid = threadIdx.x;
     const uint32_t nthreads = blockDim.x;
+    // Workgroups go to the 8 accelerator dies round-robin by index: with shift 3
+    // the working ones all sit on one die.
+    if (blockIdx.x & ((1u << a.shift) - 1u)) return;
+    const uint32_t bid = blockIdx.x >> a.shift;
+    const uint32_t nblk = gridDim.x >> a.shift;
     const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
     const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
 
@@ -137,7 +143,7 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
         in[r] = (const u32x4*)((const char*)a.in[r] + a.head * kElemSize);
     u32x4* out = (u32x4*)((char*)a.out + a.head * kElemSize);
 
-    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    for (uint64_t tile = bid; tile < ntiles; tile += nblk) {
         const uint64_t first = tile * tile_vecs;
         if (first + tile_vecs <= a.nvec) {
             u32x4 v[UNROLL][N];
@@ -166,8 +172,7 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     // Elements outside the aligned body: [0, head) and [head + nvec*kVecElems, count).
     const uint64_t body_end = a.head + a.nvec * kVecElems;
     const uint64_t nscalar = a.head + (a.count - body_end);
-    for (uint64_t k = (uint64_t)blockIdx.x * nthreads + tid; k < nscalar;
-         k += (uint64_t)gridDim.x * nthreads) {
+    for (uint64_t k = (uint64_t)bid * nthreads + tid; k < nscalar; k += (uint64_t)nblk * nthreads) {
         const uint64_t i = k < a.head ? k : body_end + (k - a.head);
         reduce_one_element<N, DT>(a, i);
     }
@@ -252,7 +257,9 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     if (grid < sgrid) grid = sgrid;
     if (shape.max_blocks && grid > shape.max_blocks) grid = shape.max_blocks;
     if (grid == 0) grid = 1;
-    if (grid > 0x7fffffffull) grid = 0x7fffffffull;
+    a.shift = shape.block_shift > 8 ? 8 : shape.block_shift;
+    if (grid > (0x7fffffffull >> a.shift)) grid = 0x7fffffffull >> a.shift;
+    grid <<= a.shift;
 
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)

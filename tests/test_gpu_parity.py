@@ -314,6 +314,33 @@ def test_allgather_bits_do_not_depend_on_split_chunk_or_rank(engine):
                     assert wl.to_numpy_bits(out).tobytes() == want, (chunk, rank, units)
 
 
+@pytest.mark.parametrize("shift", [0, 1, 2, 3])
+def test_host_kernels_confined_to_fewer_dies_give_the_same_bits(shift):
+    # the host-path grids are 2^shift times larger and only every 2^shift-th
+    # workgroup works; ragged counts, every alignment fallback of the copy
+    count = (1 << 20) + 2048 + 5
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want_ar = oracle_allreduce(bufs)
+    want_ag = oracle_allgather(bufs).tobytes()
+    for blocks in (1, 16, 100):
+        with Comm(max_host_units=10000, host_blocks=blocks, host_die_shift=shift, chunk_bytes=256 << 10,
+                  min_step_bytes=32 << 10) as comm:
+            for units in (1, 700, 10000):
+                say("die shift", shift, blocks, units)
+                fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+                fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+                out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+                fx.flex_allreduce_local(comm, bufs, out)
+                big = torch.zeros(8 * count + 8, dtype=torch.bfloat16, device=DEV)
+                for lead in (0, 1):               # 1: output 2 bytes off the inputs' alignment
+                    fx.flex_allgather_local(comm, bufs, big[lead:lead + 8 * count])
+                    torch.cuda.synchronize()
+                    assert wl.to_numpy_bits(big[lead:lead + 8 * count]).tobytes() == want_ag, (blocks, units, lead)
+                assert_same_bits(out, want_ar, "blocks %d units %d" % (blocks, units))
+    with pytest.raises(fx.FlexError):
+        Comm(host_die_shift=4).__enter__()
+
+
 @pytest.mark.parametrize("engine", ENGINES)
 @pytest.mark.parametrize("collective", ["allreduce", "allgather"])
 def test_counter_handshake_gives_the_same_bits(engine, collective):
