@@ -116,10 +116,10 @@ struct HostPath {
     hipStream_t s_up = nullptr, s_down = nullptr;  // producer / consumer stage
     std::vector<void*> pinned;
     std::vector<hipEvent_t> ev_full, ev_empty;
-    // FLEX_SYNC_COUNTERS: one pair of 32-bit counters per slot (signal memory) and
+    // FLEX_SYNC_COUNTERS: one pair of 64-bit counters per slot (signal memory) and
     // how often each slot has been used so far
-    std::vector<uint32_t*> sem_full, sem_empty;
-    std::vector<uint32_t> slot_uses;
+    std::vector<uint64_t*> sem_full, sem_empty;
+    std::vector<uint64_t> slot_uses;
     uint64_t chunk_seq = 0;  // steps staged since creation; slot = seq % num_slots
     char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
     size_t scratch_stride = 0;
@@ -192,12 +192,12 @@ struct flex_comm {
                 up_dst[j] = base + (size_t)j * cfg.chunk_bytes;
                 nn[j] = n;
             }
-            const uint32_t use = counters ? hp.slot_uses[slot] : 0;  // this is use number `use` of the slot
+            const uint64_t use = counters ? hp.slot_uses[slot] : 0;  // this is use number `use` of the slot
             // producer stage: the slot must have been drained by its previous use
             if (counters) {
                 if (use > 0)
-                    HIP_TRY(hipStreamWaitValue32(hp.s_up, hp.sem_empty[slot], use, hipStreamWaitValueGte,
-                                                 0xFFFFFFFFu));
+                    HIP_TRY(hipStreamWaitValue64(hp.s_up, hp.sem_empty[slot], use, hipStreamWaitValueGte,
+                                                 ~0ull));
             } else if (hp.chunk_seq >= nslots) {
                 HIP_TRY(hipStreamWaitEvent(hp.s_up, hp.ev_empty[slot], 0));
             }
@@ -209,9 +209,9 @@ struct flex_comm {
             }
             // hand the filled slot over to the consumer stage
             if (counters) {
-                HIP_TRY(hipStreamWriteValue32(hp.s_up, hp.sem_full[slot], use + 1, 0));
-                HIP_TRY(hipStreamWaitValue32(hp.s_down, hp.sem_full[slot], use + 1, hipStreamWaitValueGte,
-                                             0xFFFFFFFFu));
+                HIP_TRY(hipStreamWriteValue64(hp.s_up, hp.sem_full[slot], use + 1, 0));
+                HIP_TRY(hipStreamWaitValue64(hp.s_down, hp.sem_full[slot], use + 1, hipStreamWaitValueGte,
+                                             ~0ull));
             } else {
                 HIP_TRY(hipEventRecord(hp.ev_full[slot], hp.s_up));
                 HIP_TRY(hipStreamWaitEvent(hp.s_down, hp.ev_full[slot], 0));
@@ -237,7 +237,7 @@ struct flex_comm {
                     HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, hp.s_down));
             }
             if (counters) {
-                HIP_TRY(hipStreamWriteValue32(hp.s_down, hp.sem_empty[slot], use + 1, 0));
+                HIP_TRY(hipStreamWriteValue64(hp.s_down, hp.sem_empty[slot], use + 1, 0));
                 hp.slot_uses[slot] = use + 1;
             } else {
                 HIP_TRY(hipEventRecord(hp.ev_empty[slot], hp.s_down));
@@ -818,7 +818,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
                 if (c.slot_sync == FLEX_SYNC_COUNTERS) {
                     // stream memory operations need signal memory, 8 bytes per allocation
                     for (auto* vec : {&hp.sem_full, &hp.sem_empty}) {
-                        uint32_t* sem = nullptr;
+                        uint64_t* sem = nullptr;
                         CREATE_TRY(hipExtMallocWithFlags((void**)&sem, 8, hipMallocSignalMemory));
                         vec->push_back(sem);
                         CREATE_TRY(hipMemset(sem, 0, 8));

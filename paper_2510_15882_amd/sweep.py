@@ -4,6 +4,7 @@ two-stage balancer, the tensor-parallel prefill shape, and the small
 launch-bound message.  Prints one JSON line per case.
 
     python -m paper_2510_15882_amd.sweep --config 3      # 1..1024 MiB per rank, AR and AG
+    python -m paper_2510_15882_amd.sweep --config 3 --dtype f32   # same byte sizes in binary32 (or f16)
     python -m paper_2510_15882_amd.sweep --config 4      # 65536 x 5120 bf16 AllReduce, 50 calls
     python -m paper_2510_15882_amd.sweep --config 0      # 1 MiB fp32 AllReduce: latency
 
@@ -183,6 +184,8 @@ def main():
     ap.add_argument("--config", type=int, required=True, choices=[0, 3, 4])
     ap.add_argument("--windows", type=int, default=20)
     ap.add_argument("--max-mib", type=int, default=1024)
+    ap.add_argument("--dtype", default="bf16", choices=sorted(wl.DTYPE_NAMES),
+                    help="element type of the configuration 3 sweep (same byte sizes)")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs the GPU"
     fx.lib()
@@ -192,7 +195,7 @@ def main():
     elif args.config == 4:
         print(json.dumps(run_prefill()), flush=True)
     else:
-        for w in wl.sweep_workloads():
+        for w in wl.sweep_workloads(args.dtype):
             if w.bytes_per_rank > args.max_mib * wl.MIB:
                 continue
             log("case", w.name)

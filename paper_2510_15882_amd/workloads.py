@@ -50,13 +50,19 @@ CONFIGS = (
 SWEEP_MIB_PER_RANK = (1, 4, 16, 64, 256, 1024)
 
 
-def sweep_workloads():
-    """Configuration 3: AllReduce and AllGather, bf16 N(0,1), 1..1024 MiB per rank."""
+DTYPE_NAMES = {"bf16": torch.bfloat16, "f32": torch.float32, "f16": torch.float16}
+
+
+def sweep_workloads(dtype_name="bf16"):
+    """Configuration 3: AllReduce and AllGather, N(0,1), 1..1024 MiB per rank;
+    bf16 as configured, or the same byte sizes in f32 / f16."""
+    dtype = DTYPE_NAMES[dtype_name]
+    esize = torch.empty((), dtype=dtype).element_size()
     out = []
     for coll in ("allreduce", "allgather"):
         for mib in SWEEP_MIB_PER_RANK:
-            out.append(Workload(3, "%s_bf16_%dMiB" % (coll, mib), coll, torch.bfloat16,
-                                mib * MIB // 2, "normal", 1.0))
+            out.append(Workload(3, "%s_%s_%dMiB" % (coll, dtype_name, mib), coll, dtype,
+                                mib * MIB // esize, "normal", 1.0))
     return out
 
 

@@ -12,6 +12,10 @@ def test_configs_have_the_stated_shapes():
     assert wl.config(4).count == 65536 * 5120 and wl.config(4).bytes_per_rank == 640 << 20
     sweep = wl.sweep_workloads()
     assert len(sweep) == 12 and {w.bytes_per_rank >> 20 for w in sweep} == {1, 4, 16, 64, 256, 1024}
+    for name, dt in (("f32", torch.float32), ("f16", torch.float16)):
+        other = wl.sweep_workloads(name)
+        assert [w.bytes_per_rank for w in other] == [w.bytes_per_rank for w in sweep]
+        assert all(w.dtype == dt and name in w.name for w in other)
 
 
 def test_generation_is_reproducible_and_rank_distinct():
