@@ -36,6 +36,12 @@
  *     stream (side streams fork from it and join back into it by events) and
  *     return.  Stream order is the only synchronisation the caller sees; any
  *     number of calls may be queued back to back on one stream.
+ *   - Stream capture: a collective call whose whole message takes the device
+ *     path (host share 0, or a message too short to split) only launches one
+ *     kernel on the caller's stream and may be captured into a HIP graph.  A
+ *     call that would use a host path returns FLEX_ERR_STATE on a capturing
+ *     stream and enqueues nothing (its timing events are read back by the
+ *     host, which a graph replay cannot serve).
  *   - A flex_comm_t is bound to the HIP device that was current at creation
  *     and is not thread-safe; use one per thread/stream.
  *   - Structs are plain C with fixed-width fields; obtain defaults with the

@@ -346,6 +346,15 @@ struct flex_comm {
         return st;
     }
 
+    // Evaluator poll in front of a collective call: event queries are not
+    // allowed while the caller's stream is being captured, so records wait.
+    int poll_before_call(hipStream_t stream) {
+        if (ring_count == 0) return FLEX_OK;
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        HIP_TRY(hipStreamIsCapturing(stream, &capture));
+        return capture == hipStreamCaptureStatusNone ? poll(false) : FLEX_OK;
+    }
+
     int poll(bool block) {
         while (ring_count > 0) {
             bool popped = false;
@@ -411,7 +420,16 @@ struct flex_comm {
         return start[1] < count;  // some auxiliary path carries data
     }
 
-    int begin_split_call(int c, size_t bytes, bool adaptive, SizeClass* sc, TimingRecord** rec_out) {
+    // A split call records timing events that the Evaluator reads back with
+    // the host clock running; inside a stream capture they would never fire.
+    int begin_split_call(int c, size_t bytes, bool adaptive, SizeClass* sc, hipStream_t stream,
+                         TimingRecord** rec_out) {
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        HIP_TRY(hipStreamIsCapturing(stream, &capture));
+        if (capture != hipStreamCaptureStatusNone)
+            return flex::fail(FLEX_ERR_STATE,
+                              "a call that uses a host path cannot be captured into a graph: set the host "
+                              "share to 0 for captured calls");
         ++coll[c].split_calls;
         TimingRecord* rec;
         int st = acquire_record(&rec);
@@ -495,7 +513,7 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     CollState& cs = coll[c];
     ++cs.calls;
     if (count == 0) return FLEX_OK;
-    st = poll(false);
+    st = poll_before_call(stream);
     if (st) return st;
 
     const size_t es = flex::dtype_size(dtype);
@@ -515,7 +533,7 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     }
 
     TimingRecord* rec;
-    st = begin_split_call(c, count * es, adaptive, sc, &rec);
+    st = begin_split_call(c, count * es, adaptive, sc, stream, &rec);
     if (st) return st;
 
     // fork
@@ -582,7 +600,7 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
     CollState& cs = coll[c];
     ++cs.calls;
     if (count == 0) return FLEX_OK;
-    st = poll(false);
+    st = poll_before_call(stream);
     if (st) return st;
 
     const size_t es = flex::dtype_size(dtype);
@@ -606,7 +624,7 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
     }
 
     TimingRecord* rec;
-    st = begin_split_call(c, slice_bytes, adaptive, sc, &rec);
+    st = begin_split_call(c, slice_bytes, adaptive, sc, stream, &rec);
     if (st) return st;
     HIP_TRY(hipEventRecord(rec->fork, stream));
 

@@ -160,6 +160,26 @@ def run_small():
         e1.record(c.stream)
     c.stream.synchronize()
     per = e0.elapsed_time(e1) / 1000
+    # the same 1000 calls as 10 replays of a captured graph of 100
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=c.stream):
+        for _ in range(100):
+            c.call()
+    torch.cuda.synchronize()
+    graph.replay()
+    with torch.cuda.stream(c.stream):
+        e0.record(c.stream)
+        for _ in range(10):
+            graph.replay()
+        e1.record(c.stream)
+    c.stream.synchronize()
+    per_graph = e0.elapsed_time(e1) / 1000
+    want = [t.clone() for t in [c.out]]
+    c.out.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(c.out, want[0]), "graph replay changed the result"
+    del graph
     # cold: rotate over distinct buffer sets larger than the caches
     sets = [(wl.make_rank_buffers(w, "cuda:0"), torch.empty_like(c.out)) for _ in range(64)]
     torch.cuda.synchronize()
@@ -173,6 +193,7 @@ def run_small():
     cold = e0.elapsed_time(e1) / 640
     out = {"config": 0, "case": w.name, "event_bracketed_single_call_us": median(single) * 1e3,
            "back_to_back_us_per_call": per * 1e3, "back_to_back_hbm_GBs": c.hbm_bytes / per / 1e6,
+           "graph_replay_us_per_call": per_graph * 1e3, "graph_replay_hbm_GBs": c.hbm_bytes / per_graph / 1e6,
            "rotating_64_buffer_sets_us_per_call": cold * 1e3, "rotating_hbm_GBs": c.hbm_bytes / cold / 1e6,
            "note": "9 MiB of traffic per call: launch-bound; the warm figure is served by L2 / Infinity Cache"}
     c.close()

@@ -404,6 +404,52 @@ def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
 
 # ------------------------------------------------------------ three paths
 
+def test_device_path_calls_replay_from_a_graph_and_split_calls_refuse_capture():
+    # launch-bound small messages: a captured sequence of device-path calls must
+    # give the oracle's bits on every replay, with eager work between replays
+    w = wl.config(0)
+    bufs = wl.make_rank_buffers(w, DEV)
+    want_ar = oracle_allreduce(bufs)
+    slices = [b[:4099] for b in bufs]
+    want_ag = oracle_allgather(slices).tobytes()
+    outs = [torch.zeros(w.count, dtype=w.dtype, device=DEV) for _ in range(6)]
+    gathered = torch.zeros(8 * 4099, dtype=w.dtype, device=DEV)
+    with Comm(max_host_units=10000) as comm:
+        # one split call still in flight in the Evaluator's ring while capturing
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 5000)
+        fx.flex_allreduce_local(comm, bufs, outs[0])
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            with pytest.raises(fx.FlexError):                      # host share 50 %: refused, nothing enqueued
+                fx.flex_allreduce_local(comm, bufs, outs[0], stream=stream)
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 0)
+            for o in outs:
+                fx.flex_allreduce_local(comm, bufs, o, stream=stream)
+            fx.flex_allgather_local(comm, slices, gathered, stream=stream)
+        torch.cuda.synchronize()
+        for replay in range(4):
+            say("graph replay", replay)
+            for o in outs:
+                o.zero_()
+            gathered.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for k, o in enumerate(outs):
+                assert_same_bits(o, want_ar, "replay %d call %d" % (replay, k))
+            assert wl.to_numpy_bits(gathered).tobytes() == want_ag, replay
+            # the communicator still works eagerly between replays, split included
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 3000)
+            eager = torch.zeros(w.count, dtype=w.dtype, device=DEV)
+            fx.flex_allreduce_local(comm, bufs, eager)
+            torch.cuda.synchronize()
+            assert_same_bits(eager, want_ar, "eager after replay %d" % replay)
+        fx.flex_evaluator_drain(comm)
+        del graph
+
+
 @pytest.mark.parametrize("first_engine", ENGINES)
 @pytest.mark.parametrize("sync", [fx.FLEX_SYNC_EVENTS, fx.FLEX_SYNC_COUNTERS])
 def test_three_paths_give_the_same_bits(first_engine, sync):
