@@ -47,6 +47,11 @@ def median(v):
     return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
 
+def percentile(v, q):
+    v = sorted(v)
+    return v[min(len(v) - 1, max(0, int(round(q * (len(v) - 1)))))]
+
+
 def read_traffic_note():
     """HBM traffic per launch of the reduce kernel, from the committed rocprofv3
     counter summary (bytes, scaled by the copy-kernel calibration), or None."""
@@ -72,7 +77,18 @@ def cpu_baseline(oc, ar_host, ag_host, ar_bytes, ag_bytes, budget_s=10.0):
         oc.allgather(ag_host)
         times.append(time.perf_counter() - t0)
     med = median(times)
+    # the same step on one thread, best of 3 (a few seconds)
+    oc.set_threads(1)
+    single = []
+    for _ in range(3):
+        t0 = time.perf_counter()
+        oc.allreduce(ar_host)
+        oc.allgather(ag_host)
+        single.append(time.perf_counter() - t0)
+    oc.set_threads(threads)
     return {"value": (ar_bytes + ag_bytes) / med / 1e9, "unit": "GB/s", "cores": threads,
+            "single_thread": {"value": (ar_bytes + ag_bytes) / min(single) / 1e9, "unit": "GB/s",
+                              "seconds_per_step": min(single), "passes": 3, "statistic": "best"},
             "kind": "oracle", "seconds_per_step": med, "best_seconds_per_step": min(times), "passes": len(times),
             "sample": "the full step (configuration 2 AllReduce + configuration 1 AllGather), same bytes as "
                       "buffer set 0 of the GPU run; median of %d passes (about %.0f s of wall time, %d OpenMP "
@@ -268,10 +284,12 @@ def main():
                    "algorithmic_bytes_per_step": ar_bytes + ag_bytes, "library": effective},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": roofline,
-        "allreduce": {"ms_median": median(ar_ms), "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,
+        "allreduce": {"ms_median": median(ar_ms), "ms_p10": percentile(ar_ms, 0.1), "ms_p90": percentile(ar_ms, 0.9),
+                      "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,
                       "algbw_GBs": w_ar.bytes_per_rank / (median(ar_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ar1), "split_calls_timed": int(split_samples)},
-        "allgather": {"ms_median": median(ag_ms), "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
+        "allgather": {"ms_median": median(ag_ms), "ms_p10": percentile(ag_ms, 0.1), "ms_p90": percentile(ag_ms, 0.9),
+                      "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
                       "algbw_GBs": N * w_ag.bytes_per_rank / (median(ag_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ag1)},
     }

@@ -36,6 +36,11 @@ def mad(v):
     return median([abs(x - m) for x in v])
 
 
+def pct(v, q):
+    v = sorted(v)
+    return v[min(len(v) - 1, max(0, int(round(q * (len(v) - 1)))))]
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -106,6 +111,8 @@ def run_case(w, windows=20, cfg=None):
         "adaptive_ms": a, "adaptive_hbm_GBs": c.hbm_bytes / a / 1e6, "adaptive_algbw_GBs": c.alg_bytes / a / 1e6,
         "device_only_ms": d, "device_only_hbm_GBs": c.hbm_bytes / d / 1e6,
         "gain_pct": 100.0 * (d / a - 1.0), "mad_ms": [mad(adaptive_ms), mad(device_ms)],
+        "adaptive_ms_p10_p90": [pct(adaptive_ms, 0.1), pct(adaptive_ms, 0.9)],
+        "device_only_ms_p10_p90": [pct(device_ms, 0.1), pct(device_ms, 0.9)],
         "combined_faster": bool(d - a > 3 * max(mad(adaptive_ms), mad(device_ms))),
         "calls_each": calls,
     }
