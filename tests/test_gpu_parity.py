@@ -269,6 +269,92 @@ def test_alltoall_receive_buffer(dtype):
                 assert torch.all(out[n * cnt:] == 3.0)
 
 
+# ------------------------------------------ seeded random differential test
+
+def test_random_calls_of_all_four_collectives_match_the_oracle():
+    # 600 seeded cases: collective, element type, rank count, local rank, count,
+    # per-buffer misalignment, host share, engine, hand-over and step size all
+    # drawn at random; raw bit patterns as data; guard elements around the output
+    import random
+    rng = random.Random(20251015)
+    dtypes = [torch.float32, torch.bfloat16, torch.float16]
+    comms = {}
+
+    def comm_for(nranks, rank, engine, sync, chunk, shift, paths):
+        key = (nranks, rank, engine, sync, chunk, shift, paths)
+        if key not in comms:
+            if len(comms) >= 24:                         # bound the pinned memory held at once
+                torch.cuda.synchronize()
+                fx.flex_comm_destroy(comms.pop(next(iter(comms))))
+            cfg = fx.flex_config_default()
+            cfg.max_host_units, cfg.host_engine, cfg.slot_sync = 10000, engine, sync
+            cfg.chunk_bytes, cfg.host_die_shift, cfg.num_aux_paths = chunk, shift, paths
+            cfg.min_step_bytes, cfg.min_split_bytes = 8 << 10, 4 << 10
+            comms[key] = fx.flex_comm_create(nranks, rank, 16 << 20, cfg)
+        return comms[key]
+
+    try:
+        for case in range(600):
+            coll = rng.choice(["allreduce", "allgather", "reducescatter", "alltoall"])
+            dtype = rng.choice(dtypes)
+            es = 4 if dtype == torch.float32 else 2
+            nranks = rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 8, 8])
+            rank = rng.randrange(nranks)
+            count = rng.choice([0, 1, rng.randrange(2, 64), rng.randrange(64, 5000), rng.randrange(5000, 300000),
+                                1 << rng.randrange(4, 18), (1 << rng.randrange(4, 18)) + rng.choice([-1, 1, 3])])
+            per_rank = count * nranks if coll in ("reducescatter", "alltoall") else count
+            same_lead = rng.random() < 0.6               # all buffers congruent modulo 16 bytes, or not
+            lead0 = rng.randrange(0, 16 // es)
+            leads = [lead0 if same_lead else rng.randrange(0, 16 // es) for _ in range(nranks)]
+            out_lead = lead0 if rng.random() < 0.7 else rng.randrange(0, 16 // es)
+            engine, sync = rng.randrange(2), rng.randrange(2)
+            chunk = rng.choice([16 << 10, 64 << 10, 1 << 20])
+            shift, paths = rng.randrange(4), rng.choice([1, 1, 2])
+            units = rng.choice([0, 1, 37, 500, 2500, 6000, 10000])
+            units2 = rng.choice([0, 300, 2000]) if units + 2000 <= 10000 else 0
+            say("random case", case, coll, dtype, "n", nranks, "rank", rank, "count", count, "leads", leads, out_lead,
+                "engine", engine, "sync", sync, "chunk", chunk, "shift", shift, "paths", paths, "units", units, units2)
+            raw = [wl.random_bits(per_rank + 8, dtype, 7000 + 10 * case + r, DEV) for r in range(nranks)]
+            bufs = [raw[r][leads[r]:leads[r] + per_rank] for r in range(nranks)]
+            host = [wl.to_numpy_bits(b) for b in bufs]
+            out_count = {"allreduce": count, "allgather": nranks * count, "reducescatter": count,
+                         "alltoall": nranks * count}[coll]
+            guard = wl.random_bits(out_count + 24, dtype, 9000 + case, DEV, finite_only=True)
+            before = wl.to_numpy_bits(guard).copy()
+            out = guard[out_lead + 4:out_lead + 4 + out_count]
+            comm = comm_for(nranks, rank, engine, sync, chunk, shift, paths)
+            code = {"allreduce": fx.FLEX_ALLREDUCE, "allgather": fx.FLEX_ALLGATHER,
+                    "reducescatter": fx.FLEX_REDUCESCATTER, "alltoall": fx.FLEX_ALLTOALL}[coll]
+            # a one-rank communicator has no peers and therefore no host path
+            fx.flex_set_split_paths(comm, code, fx.FLEX_SPLIT_STATIC, (units, units2)[:paths] if nranks > 1 else ())
+            if coll == "allreduce":
+                fx.flex_allreduce_local(comm, bufs, out, count=count)
+                want = oc.allreduce(host) if count else None
+            elif coll == "allgather":
+                fx.flex_allgather_local(comm, bufs, out, slice_count=count)
+                want = oc.allgather(host) if count else None
+            elif coll == "reducescatter":
+                fx.flex_reducescatter_local(comm, bufs, out, recv_count=count)
+                want = oc.reducescatter(host, rank) if count else None
+            else:
+                fx.flex_alltoall_local(comm, bufs, out, count=count)
+                want = oc.alltoall(host, rank) if count else None
+            torch.cuda.synchronize()
+            after = wl.to_numpy_bits(guard)
+            lo, hi = out_lead + 4, out_lead + 4 + out_count
+            assert after[:lo].tobytes() == before[:lo].tobytes(), "case %d wrote in front of out" % case
+            assert after[hi:].tobytes() == before[hi:].tobytes(), "case %d wrote behind out" % case
+            if count:
+                if coll in ("allreduce", "reducescatter"):
+                    assert_same_bits(out, want, "case %d" % case)
+                else:
+                    assert after[lo:hi].tobytes() == want.tobytes(), "case %d" % case
+    finally:
+        torch.cuda.synchronize()
+        for h in comms.values():
+            fx.flex_comm_destroy(h)
+
+
 # ------------------------------------------------- split over both paths
 
 ENGINES = [fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
