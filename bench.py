@@ -116,6 +116,7 @@ def main():
     ap.add_argument("--copy-waves", type=int, default=0)
     ap.add_argument("--reduce-nt", type=int, default=-1)
     ap.add_argument("--copy-nt", type=int, default=-1)
+    ap.add_argument("--reduce-serial", type=int, default=-1, help="1: one load in flight per wavefront; 0: all of a tile")
     ap.add_argument("--host-engine", type=int, default=-1)
     ap.add_argument("--host-blocks", type=int, default=0)
     args = ap.parse_args()
@@ -166,10 +167,11 @@ def main():
         if val:
             setattr(cfg, key, val)
     for key, val in (("reduce_nontemporal", args.reduce_nt), ("copy_nontemporal", args.copy_nt),
-                     ("host_engine", args.host_engine)):
+                     ("host_engine", args.host_engine), ("reduce_serial_loads", args.reduce_serial)):
         if val >= 0:
             setattr(cfg, key, val)
-    for key in ("reduce_threads", "reduce_unroll", "reduce_waves_per_cu", "reduce_nontemporal", "copy_threads",
+    for key in ("reduce_threads", "reduce_serial_loads", "reduce_unroll", "reduce_waves_per_cu", "reduce_nontemporal",
+                "copy_threads",
                 "copy_unroll", "copy_waves_per_cu", "copy_nontemporal", "host_engine", "host_blocks",
                 "chunk_bytes", "num_slots", "pipeline_depth"):
         effective[key] = getattr(cfg, key)

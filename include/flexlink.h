@@ -230,7 +230,8 @@ typedef struct flex_config {
     uint32_t probe_units;        /* host share used to measure the host path's rate (default 200) */
     /* launch shapes of the two kernels; 0 = library default */
     uint32_t reduce_threads;     /* workgroup size of the N-way reduce kernel (64..1024, multiple of 64) */
-    uint32_t reduce_unroll;      /* 16-byte vectors per thread per input per tile: 1, 2 or 4 */
+    uint32_t reduce_unroll;      /* 16-byte vectors per thread per input per tile: 1, 2 or 4 (used when
+                                    reduce_serial_loads = 0) */
     uint32_t reduce_waves_per_cu;/* 0 = one workgroup per tile; else a persistent grid sized to this many
                                     wavefronts per compute unit, striding over tiles */
     uint32_t copy_threads;
@@ -253,6 +254,10 @@ typedef struct flex_config {
                                     dies; 1..3 = their grids are 2^shift times larger and only every 2^shift-th
                                     workgroup works, which keeps them on 4, 2 (default) or 1 of the dies and
                                     disturbs the device path less */
+    uint32_t reduce_serial_loads;/* device-path reduce kernel: 1 (default) = a wavefront keeps one load in flight
+                                    and asks for input r+1 only when input r has arrived; 0 = all
+                                    N * reduce_unroll loads of a tile are issued before the first add */
+    uint32_t reserved;
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

@@ -59,7 +59,7 @@ class Config(_Struct):
                 ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
                 ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("pipeline_depth", u32), ("min_step_bytes", u32),
-                ("tune_accept_check", u32), ("slot_sync", u32), ("num_aux_paths", u32), ("host_die_shift", u32),
+                ("tune_accept_check", u32), ("slot_sync", u32), ("num_aux_paths", u32), ("host_die_shift", u32), ("reduce_serial_loads", u32), ("reserved", u32),
                 ("balancer", BalancerCfg)]
 
 

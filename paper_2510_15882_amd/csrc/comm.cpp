@@ -713,7 +713,8 @@ int flex_config_default(flex_config_t* cfg) {
     // Launch shapes found best on MI355X for the 8 x 256 MiB AllReduce followed by
     // the 8 x 32 MiB AllGather on buffers that are cold in the Infinity Cache:
     // one wavefront per workgroup, one 16-byte vector per lane and input, one
-    // workgroup per tile, loads and stores both marked non-temporal.  (When the
+    // workgroup per tile, one load in flight per wavefront in the reduce, loads
+    // and stores both marked non-temporal.  (When the
     // same 256 MiB output is rewritten call after call it stays resident in the
     // 256 MB Infinity Cache and plain stores are a few percent faster.)
     cfg->reduce_threads = 64;
@@ -732,6 +733,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->slot_sync = FLEX_SYNC_EVENTS;
     cfg->num_aux_paths = 1;
     cfg->host_die_shift = 2;
+    cfg->reduce_serial_loads = 1;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
@@ -759,7 +761,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 ||
+        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 || c.reduce_serial_loads > 1 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -786,8 +788,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal,
-                       (uint32_t)cus, 0};
+    m->reduce_shape = {c.reduce_threads, c.reduce_serial_loads ? 0u : c.reduce_unroll, c.reduce_waves_per_cu,
+                       c.reduce_nontemporal, (uint32_t)cus, 0};
     m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
     // host path kernels: a fixed, small number of workgroups striding over the
     // step, so that PCIe-bound waves do not crowd the device path off the CUs

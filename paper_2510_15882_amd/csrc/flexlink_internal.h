@@ -85,7 +85,7 @@ struct Balancer {
 
 struct LaunchShape {
     uint32_t threads;       // workgroup size
-    uint32_t unroll;        // 16-byte vectors per thread per input per tile
+    uint32_t unroll;        // 16-byte vectors per thread per input per tile; reduce: 0 = one load in flight
     uint32_t waves_per_cu;  // 0 = one workgroup per tile
     uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device

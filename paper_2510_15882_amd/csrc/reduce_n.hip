@@ -3,9 +3,15 @@
 // Limitations and Future Work), fused over all N contributions.
 //
 // Pure HBM streaming for gfx950: every lane issues one 16-byte load per input
-// per unrolled step (a wavefront covers 1 KiB of each input contiguously), all
-// N * UNROLL loads of a tile are in flight before the first add, and the result
-// leaves through one 16-byte store.  No LDS and no MFMA: 7 adds per 18 bytes.
+// per unrolled step (a wavefront covers 1 KiB of each input contiguously) and
+// the result leaves through one 16-byte store.  No LDS and no MFMA: 7 adds per
+// 18 bytes.  Two load schedules: UNROLL >= 1 puts all N * UNROLL loads of a
+// tile in flight before the first add; UNROLL == 0 ("serial") keeps ONE load in
+// flight per wavefront - input r+1 is requested only after input r has arrived
+// - and leaves the latency hiding to the 32 wavefronts a compute unit holds.
+// On MI355X the serial schedule is the faster one by about 5 %: a wavefront's
+// loads return in order, so eight outstanding loads from eight streams (eight
+// different memory channels) hold each other up.
 //
 // The sum is taken strictly in rank order in binary32, starting from rank 0's
 // value, and rounded once to the element type; nothing here may be compiled
@@ -108,6 +114,45 @@ __device__ __forceinline__ u32x4 reduce_vectors(const u32x4 (&v)[N]) {
     return o;
 }
 
+// Serial schedule: one 16-byte vector of every input, summed in rank order,
+// with at most one load outstanding.  The index of the next load is passed
+// through an empty asm statement together with the value just loaded, so the
+// compiler can neither issue the next load early nor drop the dependence.
+template <int N, int DT, bool LDNT>
+__device__ __forceinline__ u32x4 reduce_serial(const u32x4* const (&in)[N], uint64_t idx) {
+    constexpr int kAcc = DT == kF32 ? 4 : 8;
+    float acc[kAcc];
+    u32x4 v = load16<LDNT>(in[0] + idx);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (DT != kF32) {
+            acc[2 * w] = widen_low<DT>(v[w]);
+            acc[2 * w + 1] = widen_high<DT>(v[w]);
+        } else {
+            acc[w] = __uint_as_float(v[w]);
+        }
+    }
+#pragma unroll
+    for (int r = 1; r < N; ++r) {
+        asm volatile("" : "+v"(idx) : "v"(v[0]));
+        v = load16<LDNT>(in[r] + idx);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (DT != kF32) {
+                acc[2 * w] = acc[2 * w] + widen_low<DT>(v[w]);
+                acc[2 * w + 1] = acc[2 * w + 1] + widen_high<DT>(v[w]);
+            } else {
+                acc[w] = acc[w] + __uint_as_float(v[w]);
+            }
+        }
+    }
+    u32x4 o;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        o[w] = DT != kF32 ? (narrow<DT>(acc[2 * w]) | (narrow<DT>(acc[2 * w + 1]) << 16)) : __float_as_uint(acc[w]);
+    return o;
+}
+
 template <int N, int DT>
 __device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t i) {
     if (DT != kF32) {
@@ -134,7 +179,9 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     if (blockIdx.x & ((1u << a.shift) - 1u)) return;
     const uint32_t bid = blockIdx.x >> a.shift;
     const uint32_t nblk = gridDim.x >> a.shift;
-    const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
+    constexpr bool kSerial = UNROLL == 0;
+    constexpr int kUnroll = kSerial ? 1 : UNROLL;
+    const uint64_t tile_vecs = (uint64_t)nthreads * kUnroll;
     const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
 
     const u32x4* in[N];
@@ -145,19 +192,22 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
 
     for (uint64_t tile = bid; tile < ntiles; tile += nblk) {
         const uint64_t first = tile * tile_vecs;
-        if (first + tile_vecs <= a.nvec) {
-            u32x4 v[UNROLL][N];
+        if (kSerial) {
+            const uint64_t idx = first + tid;
+            if (idx < a.nvec) store16<STNT>(out + idx, reduce_serial<N, DT, LDNT>(in, idx));
+        } else if (first + tile_vecs <= a.nvec) {
+            u32x4 v[kUnroll][N];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
                 for (int r = 0; r < N; ++r)
                     v[u][r] = load16<LDNT>(in[r] + first + (uint64_t)u * nthreads + tid);
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < kUnroll; ++u)
                 store16<STNT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, DT>(v[u]));
         } else {
             // ragged last tile
-            for (int u = 0; u < UNROLL; ++u) {
+            for (int u = 0; u < kUnroll; ++u) {
                 const uint64_t idx = first + (uint64_t)u * nthreads + tid;
                 if (idx < a.nvec) {
                     u32x4 v[N];
@@ -193,6 +243,7 @@ template <int N, int DT>
 int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
              hipStream_t stream) {
     switch (unroll) {
+        case 0: return launch_one<N, DT, 0>(a, grid, threads, nt, stream);
         case 1: return launch_one<N, DT, 1>(a, grid, threads, nt, stream);
         case 2: return launch_one<N, DT, 2>(a, grid, threads, nt, stream);
         default: return launch_one<N, DT, 4>(a, grid, threads, nt, stream);
@@ -242,8 +293,8 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     a.nvec = (count - head) / vec_elems;
 
     const uint32_t threads = shape.threads;
-    const uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : 4;
-    const uint64_t tile_vecs = (uint64_t)threads * unroll;
+    const uint32_t unroll = shape.unroll <= 2 ? shape.unroll : 4;  // 0 = serial schedule
+    const uint64_t tile_vecs = (uint64_t)threads * (unroll ? unroll : 1);
     const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
     const uint64_t nscalar = count - a.nvec * vec_elems;
     const uint64_t scalar_blocks = (nscalar + threads - 1) / threads;

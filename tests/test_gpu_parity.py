@@ -79,12 +79,14 @@ COUNTS = [0, 1, 7, 8, 9, 2047, 2048, 2049, 65536, (1 << 20) + 3]
 
 # ------------------------------------------------------------ device path
 
+@pytest.mark.parametrize("serial", [1, 0])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("nranks", [1, 2, 3, 8])
-def test_allreduce_device_path_all_counts(dtype, nranks):
-    with Comm(nranks=nranks) as comm:
+def test_allreduce_device_path_all_counts(dtype, nranks, serial):
+    # serial: one load in flight per wavefront (the default); 0: every load of a tile at once
+    with Comm(nranks=nranks, reduce_serial_loads=serial) as comm:
         for count in COUNTS:
-            say("allreduce device", dtype, nranks, count)
+            say("allreduce device", dtype, nranks, count, "serial", serial)
             bufs = [wl.random_bits(count, dtype, 11 * r + count % 97, DEV, finite_only=True) for r in range(nranks)]
             # keep exponents within reach of each other so that roundings matter
             bufs = [torch.ldexp(torch.frexp(b.float())[0], torch.tensor(r % 3, device=DEV)).to(dtype) for r, b in enumerate(bufs)]
@@ -95,10 +97,11 @@ def test_allreduce_device_path_all_counts(dtype, nranks):
             assert torch.all(out[count:] == 7.0), "wrote past the end"
 
 
+@pytest.mark.parametrize("serial", [1, 0])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
-def test_allreduce_raw_bit_patterns_and_specials(dtype):
+def test_allreduce_raw_bit_patterns_and_specials(dtype, serial):
     count = 300007
-    with Comm() as comm:
+    with Comm(reduce_serial_loads=serial) as comm:
         bufs = [wl.random_bits(count, dtype, 500 + r, DEV) for r in range(8)]   # NaN, inf, denormals included
         out = torch.empty(count, dtype=dtype, device=DEV)
         fx.flex_allreduce_local(comm, bufs, out)
@@ -202,16 +205,17 @@ def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want_ar = oracle_allreduce(bufs)
     want_ag = oracle_allgather(bufs)
-    with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
-              copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves, reduce_nontemporal=nt,
-              copy_nontemporal=nt) as comm:
-        out = torch.empty(count, dtype=torch.bfloat16, device=DEV)
-        fx.flex_allreduce_local(comm, bufs, out)
-        out2 = torch.empty(8 * count, dtype=torch.bfloat16, device=DEV)
-        fx.flex_allgather_local(comm, bufs, out2)
-        torch.cuda.synchronize()
-        assert_same_bits(out, want_ar, "allreduce")
-        assert wl.to_numpy_bits(out2).tobytes() == want_ag.tobytes()
+    for serial in (0, 1):
+        with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
+                  reduce_serial_loads=serial, copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves,
+                  reduce_nontemporal=nt, copy_nontemporal=nt) as comm:
+            out = torch.empty(count, dtype=torch.bfloat16, device=DEV)
+            fx.flex_allreduce_local(comm, bufs, out)
+            out2 = torch.empty(8 * count, dtype=torch.bfloat16, device=DEV)
+            fx.flex_allgather_local(comm, bufs, out2)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want_ar, "allreduce, serial %d" % serial)
+            assert wl.to_numpy_bits(out2).tobytes() == want_ag.tobytes()
 
 
 # ---------------------------------------------------------- ReduceScatter
@@ -289,6 +293,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
             cfg = fx.flex_config_default()
             cfg.max_host_units, cfg.host_engine, cfg.slot_sync = 10000, engine, sync
             cfg.chunk_bytes, cfg.host_die_shift, cfg.num_aux_paths = chunk, shift, paths
+            cfg.reduce_serial_loads = (engine + sync + shift) % 2
             cfg.min_step_bytes, cfg.min_split_bytes = 8 << 10, 4 << 10
             comms[key] = fx.flex_comm_create(nranks, rank, 16 << 20, cfg)
         return comms[key]

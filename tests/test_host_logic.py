@@ -35,7 +35,7 @@ def test_struct_layout_defaults_come_through():
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
     assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 16, 4, 256 << 10)
-    assert c.tune_accept_check == 1 and c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2
+    assert c.tune_accept_check == 1 and c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
     b = c.balancer
     assert (b.share_total, b.initial_step, b.stability_required, b.max_tune_iters, b.window,
             b.runtime_step) == (10000, 64, 3, 100, 10, 4)
