@@ -116,7 +116,7 @@ def main():
     ap.add_argument("--copy-waves", type=int, default=0)
     ap.add_argument("--reduce-nt", type=int, default=-1)
     ap.add_argument("--copy-nt", type=int, default=-1)
-    ap.add_argument("--reduce-serial", type=int, default=-1, help="1: one load in flight per wavefront; 0: all of a tile")
+    ap.add_argument("--reduce-serial", type=int, default=-1, help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
     ap.add_argument("--host-engine", type=int, default=-1)
     ap.add_argument("--host-blocks", type=int, default=0)
     args = ap.parse_args()

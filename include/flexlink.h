@@ -254,9 +254,11 @@ typedef struct flex_config {
                                     dies; 1..3 = their grids are 2^shift times larger and only every 2^shift-th
                                     workgroup works, which keeps them on 4, 2 (default) or 1 of the dies and
                                     disturbs the device path less */
-    uint32_t reduce_serial_loads;/* device-path reduce kernel: 1 (default) = a wavefront keeps one load in flight
-                                    and asks for input r+1 only when input r has arrived; 0 = all
-                                    N * reduce_unroll loads of a tile are issued before the first add */
+    uint32_t reduce_serial_loads;/* device-path reduce kernel.  2 = a wavefront keeps one load in flight and asks
+                                    for input r+1 only when input r has arrived; 0 = all N * reduce_unroll
+                                    loads of a tile are issued before the first add; 1 (default) = the first
+                                    for launches of at least 16 tiles per compute unit (4 MiB of bf16 per
+                                    rank on MI355X), the second for shorter ones */
     uint32_t reserved;
     flex_balancer_cfg_t balancer;
 } flex_config_t;

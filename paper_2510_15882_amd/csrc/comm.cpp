@@ -761,7 +761,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 || c.reduce_serial_loads > 1 ||
+        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 || c.reduce_serial_loads > 2 ||
         b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
         c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -788,8 +788,11 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_serial_loads ? 0u : c.reduce_unroll, c.reduce_waves_per_cu,
-                       c.reduce_nontemporal, (uint32_t)cus, 0};
+    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal,
+                       (uint32_t)cus, 0};
+    // 16 tiles per compute unit: half of the wavefront slots of the chip
+    m->reduce_shape.serial_min_tiles = c.reduce_serial_loads == 2 ? 1u
+                                       : c.reduce_serial_loads == 1 ? 16u * (uint32_t)cus : 0u;
     m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
     // host path kernels: a fixed, small number of workgroups striding over the
     // step, so that PCIe-bound waves do not crowd the device path off the CUs

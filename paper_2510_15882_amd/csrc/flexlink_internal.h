@@ -85,7 +85,7 @@ struct Balancer {
 
 struct LaunchShape {
     uint32_t threads;       // workgroup size
-    uint32_t unroll;        // 16-byte vectors per thread per input per tile; reduce: 0 = one load in flight
+    uint32_t unroll;        // 16-byte vectors per thread per input per tile
     uint32_t waves_per_cu;  // 0 = one workgroup per tile
     uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device
@@ -93,6 +93,10 @@ struct LaunchShape {
     // The grid is made 2^block_shift times larger and only every 2^block_shift-th
     // workgroup works: 3 keeps the working workgroups on one of the 8 dies.
     uint32_t block_shift = 0;
+    // Reduce kernel: a launch of at least this many wavefront tiles (1 KiB per
+    // input) keeps one load in flight per wavefront instead of all of a tile's
+    // loads (0 = never).
+    uint32_t serial_min_tiles = 0;
 };
 
 // Enqueue out[i] = sum over r (rank order) of in[r][i], i in [0, count), on

@@ -9,9 +9,11 @@
 // tile in flight before the first add; UNROLL == 0 ("serial") keeps ONE load in
 // flight per wavefront - input r+1 is requested only after input r has arrived
 // - and leaves the latency hiding to the 32 wavefronts a compute unit holds.
-// On MI355X the serial schedule is the faster one by about 5 %: a wavefront's
-// loads return in order, so eight outstanding loads from eight streams (eight
-// different memory channels) hold each other up.
+// On MI355X the serial schedule is the faster one by 3-7 % for messages of
+// 4 MiB and more per rank: a wavefront's loads return in order, so eight
+// outstanding loads from eight streams (eight different memory channels) hold
+// each other up.  Short messages, whose time is one wavefront's lifetime, are
+// faster with all loads in flight; the launcher chooses by tile count.
 //
 // The sum is taken strictly in rank order in binary32, starting from rank 0's
 // value, and rounded once to the element type; nothing here may be compiled
@@ -293,7 +295,11 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     a.nvec = (count - head) / vec_elems;
 
     const uint32_t threads = shape.threads;
-    const uint32_t unroll = shape.unroll <= 2 ? shape.unroll : 4;  // 0 = serial schedule
+    uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : 4;
+    // The serial schedule pays N load latencies per tile: it wins once the
+    // message keeps every wavefront slot of the chip busy several times over,
+    // and loses on short messages whose time is one wavefront's lifetime.
+    if (shape.serial_min_tiles && (a.nvec + 63) / 64 >= shape.serial_min_tiles) unroll = 0;  // 1 KiB tiles
     const uint64_t tile_vecs = (uint64_t)threads * (unroll ? unroll : 1);
     const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
     const uint64_t nscalar = count - a.nvec * vec_elems;

@@ -79,11 +79,12 @@ COUNTS = [0, 1, 7, 8, 9, 2047, 2048, 2049, 65536, (1 << 20) + 3]
 
 # ------------------------------------------------------------ device path
 
-@pytest.mark.parametrize("serial", [1, 0])
+@pytest.mark.parametrize("serial", [2, 0])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("nranks", [1, 2, 3, 8])
 def test_allreduce_device_path_all_counts(dtype, nranks, serial):
-    # serial: one load in flight per wavefront (the default); 0: every load of a tile at once
+    # serial 2: one load in flight per wavefront at every size; 0: every load of a tile at once
+    # (the default, 1, picks between the two by message size)
     with Comm(nranks=nranks, reduce_serial_loads=serial) as comm:
         for count in COUNTS:
             say("allreduce device", dtype, nranks, count, "serial", serial)
@@ -97,7 +98,7 @@ def test_allreduce_device_path_all_counts(dtype, nranks, serial):
             assert torch.all(out[count:] == 7.0), "wrote past the end"
 
 
-@pytest.mark.parametrize("serial", [1, 0])
+@pytest.mark.parametrize("serial", [2, 0])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_allreduce_raw_bit_patterns_and_specials(dtype, serial):
     count = 300007
@@ -205,7 +206,7 @@ def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want_ar = oracle_allreduce(bufs)
     want_ag = oracle_allgather(bufs)
-    for serial in (0, 1):
+    for serial in (0, 1, 2):
         with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
                   reduce_serial_loads=serial, copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves,
                   reduce_nontemporal=nt, copy_nontemporal=nt) as comm:
@@ -293,7 +294,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
             cfg = fx.flex_config_default()
             cfg.max_host_units, cfg.host_engine, cfg.slot_sync = 10000, engine, sync
             cfg.chunk_bytes, cfg.host_die_shift, cfg.num_aux_paths = chunk, shift, paths
-            cfg.reduce_serial_loads = (engine + sync + shift) % 2
+            cfg.reduce_serial_loads = (engine + sync + shift) % 3
             cfg.min_step_bytes, cfg.min_split_bytes = 8 << 10, 4 << 10
             comms[key] = fx.flex_comm_create(nranks, rank, 16 << 20, cfg)
         return comms[key]
