@@ -18,7 +18,9 @@ nccl-tests style loops measure) are reported under extras.warm_same_buffers*.
 Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
 timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
 dominant kernel (the N-way reduce) against the 8 TB/s HBM3E peak from per-launch
-HIP-event timings taken inside the timed region; `cpu_baseline` is the CPU
+HIP-event timings taken inside the timed region (every --event-every-th step,
+default 4: each event is a packet of its own on the stream and three per step
+cost 2 % of the step); `cpu_baseline` is the CPU
 oracle timed on this machine's host cores.
 """
 import argparse
@@ -108,6 +110,9 @@ def main():
                     help="only launch a plain copy of known size (1-rank AllGather of 1 GiB, 10 launches): the "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed warm / static-split legs")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="bracket the two calls of every K-th timed step with HIP events (per-kernel times for the "
+                         "roofline); the event packets themselves cost a few microseconds of stream time each")
     ap.add_argument("--reduce-threads", type=int, default=0)
     ap.add_argument("--reduce-unroll", type=int, default=0)
     ap.add_argument("--reduce-waves", type=int, default=0)
@@ -233,16 +238,22 @@ def main():
     s_ar0 = stats(fx.FLEX_ALLREDUCE, w_ar)
 
     # ---- timed region: exactly --steps steps --------------------------------
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    every = max(1, args.event_every)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(0, args.steps, every)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     with torch.cuda.stream(stream):
         for k in range(args.steps):
-            ev[k][0].record(stream)
-            ar(k)
-            ev[k][1].record(stream)
-            ag(k)
-            ev[k][2].record(stream)
+            if k % every == 0:
+                e = ev[k // every]
+                e[0].record(stream)
+                ar(k)
+                e[1].record(stream)
+                ag(k)
+                e[2].record(stream)
+            else:
+                ar(k)
+                ag(k)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     fx.flex_evaluator_drain(comm)
@@ -265,7 +276,8 @@ def main():
         how = "Evaluator events fork->device-path-done, mean of %d split calls" % split_samples
     else:
         kern_ms = sum(ar_ms) / len(ar_ms)
-        how = "HIP events around each launch on the launch stream, mean of %d launches" % len(ar_ms)
+        how = ("HIP events on the launch stream around every %slaunch of the timed region, mean of %d launches"
+               % ("" if every == 1 else "%d-th " % every, len(ar_ms)))
     bytes_per_elem = (N + 1) * 2
     achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "reduce_n_kernel<8, bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
