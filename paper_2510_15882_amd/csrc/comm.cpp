@@ -761,9 +761,9 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 || c.host_die_shift > 3 || c.reduce_serial_loads > 2 ||
-        b.share_total == 0 || c.max_host_units > b.share_total || c.split_align_elems == 0 ||
-        c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
+        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
+        c.host_die_shift > 3 || c.reduce_serial_loads > 2 || b.share_total == 0 ||
+        c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
         !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_create: configuration out of range");
 
