@@ -227,6 +227,28 @@ def test_binding_structs_have_the_library_layout():
     assert fx.flex_struct_sizes() == want
 
 
+def test_header_is_plain_c_and_its_structs_have_the_library_layout(tmp_path):
+    # the boundary is a C ABI: the header must compile as strict C99 and as C++
+    # with no other header, and a C compiler must lay the structs out as the
+    # library does
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text(
+        '#include "flexlink.h"\n#include <stdio.h>\n'
+        'int main(void) { printf("%zu %zu %zu %zu %zu\\n", sizeof(flex_balancer_cfg_t), '
+        'sizeof(flex_balancer_state_t), sizeof(flex_config_t), sizeof(flex_stats_t), sizeof(flex_tune_result_t)); '
+        'return (FLEX_MAX_RANKS == 8 && FLEX_MAX_PATHS == 4 && FLEX_ALLTOALL == 3) ? 0 : 1; }\n')
+    exe = tmp_path / "sizes"
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, str(src), "-o", str(exe)],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(x) for x in out] == fx.flex_struct_sizes()
+    cpp = tmp_path / "only_header.cpp"
+    cpp.write_text('#include "flexlink.h"\nint main() { return sizeof(flex_config_t) ? 0 : 1; }\n')
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     from paper_2510_15882_amd import build
     monkeypatch.setattr(fx, "_lib", None)
