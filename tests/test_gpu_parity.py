@@ -847,3 +847,22 @@ def test_invalid_arguments_are_rejected_without_enqueueing():
         fx.flex_allreduce_local(comm, bufs, out)
         torch.cuda.synchronize()
         assert_same_bits(out, oracle_allreduce(bufs), "after errors")
+
+
+# ------------------------------------------------- the C ABI from plain C
+
+def test_plain_c_program_through_the_c_abi():
+    # no Python between the caller and the library: a C99 program linked against
+    # libflexlink.so, the HIP runtime and the C oracle (built beforehand by
+    # tests/c_abi/build.py), run as one child process
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "c_abi_check")
+    if not os.path.exists(exe):
+        pytest.skip("tests/c_abi/c_abi_check is not built (python -m tests.c_abi.build, or the build entry point)")
+    torch.cuda.synchronize()
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    say(run.stdout, run.stderr)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert run.stdout.count("ok  ") == 8 and "C ABI check passed" in run.stdout
+
