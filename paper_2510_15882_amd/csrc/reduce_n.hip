@@ -10,9 +10,9 @@
 // flight per wavefront - input r+1 is requested only after input r has arrived
 // - and leaves the latency hiding to the 32 wavefronts a compute unit holds.
 // On MI355X the serial schedule is the faster one by 3-7 % for messages of
-// 4 MiB and more per rank: a wavefront's loads return in order, so eight
-// outstanding loads from eight streams (eight different memory channels) hold
-// each other up.  Short messages, whose time is one wavefront's lifetime, are
+// 4 MiB and more per rank (a wavefront's loads return in order, so eight
+// outstanding loads to eight streams can hold each other up; measured, not
+// derived).  Short messages, whose time is one wavefront's lifetime, are
 // faster with all loads in flight; the launcher chooses by tile count.
 //
 // The sum is taken strictly in rank order in binary32, starting from rank 0's
