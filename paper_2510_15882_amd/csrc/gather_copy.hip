@@ -84,7 +84,9 @@ __global__ void gather_copy_kernel(CopyArgs a) {
 
     const uint32_t tid = threadIdx.x;
     const uint32_t nthreads = blockDim.x;
-    uint64_t head = (16 - ((uintptr_t)s & 15)) & 15;
+    // body from where the destination reaches a 1 KiB boundary: every wavefront
+    // then stores whole, tile-aligned lines (the source is 16-byte aligned there)
+    uint64_t head = (1024 - ((uintptr_t)d & 1023)) & 1023;
     if (head > bytes) head = bytes;
     const uint64_t nvec = (bytes - head) / 16;
     const u32x4* in = (const u32x4*)(s + head);
@@ -108,7 +110,7 @@ __global__ void gather_copy_kernel(CopyArgs a) {
         }
     }
 
-    // bytes outside the aligned body (at most 15 on each side)
+    // bytes outside the aligned body (at most 1023 in front, 15 behind)
     const uint64_t body_end = head + nvec * 16;
     const uint64_t nloose = head + (bytes - body_end);
     if (bid == 0) {
