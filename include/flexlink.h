@@ -340,8 +340,9 @@ int flex_comm_destroy(flex_comm_t* comm);
  * peers' elements [split, count) travel through the pinned transit buffers on
  * the side streams and are reduced there, in the same rank order, together
  * with the local rank's elements read in place.
- * Pointers need no particular alignment (16-byte aligned ones take the fast
- * path).  out may be the same buffer as rank_bufs[rank]; any other overlap
+ * Pointers need element alignment only; fastest when every pointer has the
+ * same offset within 16 bytes (any common offset runs at the aligned rate,
+ * differing offsets cost 10-25 %).  out may be the same buffer as rank_bufs[rank]; any other overlap
  * between out and an input is undefined.
  * Errors: INVALID_ARG (null comm/rank_bufs/out/any rank pointer with count > 0,
  * count * size > max_bytes_per_rank), UNSUPPORTED (dtype, op), HIP. */

@@ -5,7 +5,8 @@
 //
 // Pure HBM streaming for gfx950: blockIdx.y selects the slice, lanes move
 // 16-byte vectors so that a wavefront covers 1 KiB contiguously, UNROLL loads
-// are in flight per lane before the first store.  Bytes are never interpreted.
+// are in flight per lane before the first store.  Bytes are never interpreted;
+// source and destination may sit at any byte addresses.
 #include <hip/hip_runtime.h>
 
 #include "flexlink_internal.h"
@@ -13,6 +14,11 @@
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The same vector at any byte address: gfx950 under ROCm serves vector loads
+// from unaligned addresses (a load that straddles a line costs a second line
+// access), so source and destination need not agree within 16 bytes.  Only
+// the stores are kept aligned.
+typedef u32x4 u32x4_src __attribute__((aligned(1)));
 
 struct CopyArgs {
     const void* src[FLEX_MAX_RANKS];
@@ -22,7 +28,7 @@ struct CopyArgs {
 };
 
 template <bool NT>
-__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+__device__ __forceinline__ u32x4 load16(const u32x4_src* p) {
     if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
@@ -33,27 +39,6 @@ __device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
         __builtin_nontemporal_store(v, p);
     else
         *p = v;
-}
-
-// Copy in granules of sizeof(G) bytes when source and destination only agree
-// modulo sizeof(G): byte-wise head until both are G-aligned, G-wise body,
-// byte-wise tail.  All workgroups of the slice stride over it together.
-template <typename G>
-__device__ void copy_granules(const char* s, char* d, uint64_t bytes, uint32_t bid, uint32_t nblk) {
-    const uint64_t gtid = (uint64_t)bid * blockDim.x + threadIdx.x;
-    const uint64_t gsize = (uint64_t)nblk * blockDim.x;
-    uint64_t head = (sizeof(G) - ((uintptr_t)s & (sizeof(G) - 1))) & (sizeof(G) - 1);
-    if (head > bytes) head = bytes;
-    const uint64_t nbody = (bytes - head) / sizeof(G);
-    const G* sb = (const G*)(s + head);
-    G* db = (G*)(d + head);
-    for (uint64_t k = gtid; k < nbody; k += gsize) db[k] = sb[k];
-    const uint64_t body_end = head + nbody * sizeof(G);
-    const uint64_t nloose = head + (bytes - body_end);
-    for (uint64_t k = gtid; k < nloose; k += gsize) {
-        const uint64_t i = k < head ? k : body_end + (k - head);
-        d[i] = s[i];
-    }
 }
 
 template <int UNROLL, bool LDNT, bool STNT>
@@ -70,26 +55,15 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     const uint32_t bid = blockIdx.x >> a.shift;
     const uint32_t nblk = gridDim.x >> a.shift;
 
-    const uintptr_t diff = (uintptr_t)s ^ (uintptr_t)d;
-    if (diff & 15) {
-        // source and destination disagree within a 16-byte line
-        if ((diff & 3) == 0)
-            copy_granules<uint32_t>(s, d, bytes, bid, nblk);
-        else if ((diff & 1) == 0)
-            copy_granules<uint16_t>(s, d, bytes, bid, nblk);
-        else
-            copy_granules<uint8_t>(s, d, bytes, bid, nblk);
-        return;
-    }
-
     const uint32_t tid = threadIdx.x;
     const uint32_t nthreads = blockDim.x;
     // body from where the destination reaches a 1 KiB boundary: every wavefront
-    // then stores whole, tile-aligned lines (the source is 16-byte aligned there)
+    // then stores whole, tile-aligned lines (a source at the same offset within
+    // 1 KiB, the common case, is aligned there too)
     uint64_t head = (1024 - ((uintptr_t)d & 1023)) & 1023;
     if (head > bytes) head = bytes;
     const uint64_t nvec = (bytes - head) / 16;
-    const u32x4* in = (const u32x4*)(s + head);
+    const u32x4_src* in = (const u32x4_src*)(s + head);
     u32x4* out = (u32x4*)(d + head);
     const uint64_t tile_vecs = (uint64_t)nthreads * UNROLL;
     const uint64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;

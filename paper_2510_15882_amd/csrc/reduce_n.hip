@@ -25,6 +25,11 @@
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The same vector at any element-aligned address.  gfx950 under ROCm serves
+// vector loads from unaligned addresses (a load that straddles a line costs a
+// second line access, nothing else), so an input need not share the output's
+// offset within 16 bytes: only the stores are kept aligned.
+typedef u32x4 u32x4_in __attribute__((aligned(2)));
 
 struct ReduceArgs {
     const void* in[FLEX_MAX_RANKS];
@@ -36,7 +41,7 @@ struct ReduceArgs {
 };
 
 template <bool NT>
-__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+__device__ __forceinline__ u32x4 load16(const u32x4_in* p) {
     if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
@@ -121,7 +126,7 @@ __device__ __forceinline__ u32x4 reduce_vectors(const u32x4 (&v)[N]) {
 // through an empty asm statement together with the value just loaded, so the
 // compiler can neither issue the next load early nor drop the dependence.
 template <int N, int DT, bool LDNT>
-__device__ __forceinline__ u32x4 reduce_serial(const u32x4* const (&in)[N], uint64_t idx) {
+__device__ __forceinline__ u32x4 reduce_serial(const u32x4_in* const (&in)[N], uint64_t idx) {
     constexpr int kAcc = DT == kF32 ? 4 : 8;
     float acc[kAcc];
     u32x4 v = load16<LDNT>(in[0] + idx);
@@ -186,10 +191,10 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     const uint64_t tile_vecs = (uint64_t)nthreads * kUnroll;
     const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
 
-    const u32x4* in[N];
+    const u32x4_in* in[N];
 #pragma unroll
     for (int r = 0; r < N; ++r)
-        in[r] = (const u32x4*)((const char*)a.in[r] + a.head * kElemSize);
+        in[r] = (const u32x4_in*)((const char*)a.in[r] + a.head * kElemSize);
     u32x4* out = (u32x4*)((char*)a.out + a.head * kElemSize);
 
     for (uint64_t tile = bid; tile < ntiles; tile += nblk) {
@@ -283,21 +288,14 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     a.out = out;
     a.count = count;
 
-    // The 16-byte body needs every pointer at the same offset within a
-    // 16-byte line, and that offset a whole number of elements.  The body then
-    // starts where the output reaches a 1 KiB boundary, so that every
-    // wavefront stores whole, tile-aligned lines (measured on MI355X: a body
-    // that starts 16 or 64 bytes off a line is 15 % slower, one that starts
-    // 256 bytes off a 1 KiB boundary 7 %); inputs that share the output's
-    // offset within 1 KiB, the common case, come out aligned with it.
-    const uintptr_t mis = (uintptr_t)out & 15;
-    bool congruent = (mis % esize) == 0;
-    for (int r = 0; r < n; ++r) congruent = congruent && (((uintptr_t)in[r] & 15) == mis);
-    uint64_t head = count;
-    if (congruent) {
-        head = ((kTileBytes - ((uintptr_t)out & (kTileBytes - 1))) & (kTileBytes - 1)) / esize;
-        if (head > count) head = count;
-    }
+    // The vector body starts where the output reaches a 1 KiB boundary, so
+    // that every wavefront stores whole, tile-aligned lines (measured on
+    // MI355X: a body that starts 16 or 64 bytes off a line is 15 % slower, one
+    // that starts 256 bytes off a 1 KiB boundary 7 %).  Inputs that share the
+    // output's offset within 1 KiB, the common case, come out aligned with it;
+    // any other input is read through unaligned vector loads.
+    uint64_t head = ((kTileBytes - ((uintptr_t)out & (kTileBytes - 1))) & (kTileBytes - 1)) / esize;
+    if (head > count) head = count;
     a.head = head;
     a.nvec = (count - head) / vec_elems;
 
