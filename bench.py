@@ -10,7 +10,7 @@ Inputs are resident in HBM before the timed region starts.
 
 Successive steps rotate over --buffer-sets independent sets of input and output
 buffers (default 3, about 8 GiB in all), so that every byte a step touches was
-last touched several GiB of traffic earlier: the 256 MB Infinity Cache cannot
+last touched several GiB of traffic earlier: the 256 MB memory-side cache cannot
 keep an output buffer resident from one call to the next and the HBM traffic
 equals the algorithmic bytes.  The same-buffers-every-call figures (what
 nccl-tests style loops measure) are reported under extras.warm_same_buffers*.
@@ -18,14 +18,19 @@ nccl-tests style loops measure) are reported under extras.warm_same_buffers*.
 Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
 timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
 dominant kernel (the N-way reduce) against the 8 TB/s HBM3E peak from per-launch
-HIP-event timings taken inside the timed region (every --event-every-th step,
-default 4: each event is a packet of its own on the stream and three per step
-cost 2 % of the step); `cpu_baseline` is the CPU
-oracle timed on this machine's host cores.
+HIP-event timings taken inside the timed region (every step when --steps <= 50,
+else every 4th: each event is a packet of its own on the stream and three per
+step cost 2 % of the step); `host_path` gives configuration 2's static 5 / 12 /
+22 % splits with the PCIe rate per direction against 64 GB/s; `extras.ceilings`
+is what plain probe kernels reach on this very box (bench_ceilings.hip);
+`cpu_baseline` is the CPU oracle timed on this machine's host cores.
 """
 import argparse
+import ctypes
+import hashlib
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -37,6 +42,13 @@ HBM_PEAK_GBS = 8000.0
 PCIE_PEAK_GBS = 64.0
 METRIC = "AllReduce/AllGather local-share GB/s at 256MB (8 sim ranks); % HBM peak"
 N = 8
+
+CEILINGS_SRC = os.path.join(ROOT, "bench_ceilings.hip")
+CEILINGS_LIB = os.path.join(ROOT, "libflex_ceilings.so")
+CEILINGS_EXE = os.path.join(ROOT, "bench_ceilings")
+PMC_SUMMARY = os.path.join("profiles", "reduce_n_allreduce_bf16_256MiB_pmc.txt")
+KERNEL_SOURCES = [os.path.join("paper_2510_15882_amd", "csrc", f)
+                  for f in ("reduce_n.hip", "gather_copy.hip", "flexlink_internal.h")]
 
 
 def log(*a):
@@ -54,17 +66,58 @@ def percentile(v, q):
     return v[min(len(v) - 1, max(0, int(round(q * (len(v) - 1)))))]
 
 
-def read_traffic_note():
-    """HBM traffic per launch of the reduce kernel, from the committed rocprofv3
-    counter summary (bytes, scaled by the copy-kernel calibration), or None."""
-    path = os.path.join(ROOT, "profiles", "reduce_n_allreduce_bf16_256MiB_pmc.txt")
+def build_ceilings():
+    """Compile bench_ceilings.hip for gfx950: a shared library this script loads
+    and a stand-alone program for rocprofv3."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    common = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+              "-packed-fp32-ops", "-Wall", "-Wextra", CEILINGS_SRC]
+    for extra, target in ((["-shared", "-fPIC"], CEILINGS_LIB), (["-DCEILINGS_MAIN"], CEILINGS_EXE)):
+        tmp = target + ".tmp.%d" % os.getpid()
+        subprocess.check_call(common + extra + ["-o", tmp])
+        os.replace(tmp, target)
+
+
+def measure_ceilings(what=3, reps=6):
+    """HBM and PCIe ceilings of this machine from the probe kernels, or a note why not."""
+    if not os.path.exists(CEILINGS_LIB):
+        return {"note": "libflex_ceilings.so is not built (python -c 'import bench; bench.build_ceilings()')"}
+    lib = ctypes.CDLL(CEILINGS_LIB)
+    lib.flex_ceilings_run.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int]
+    buf = ctypes.create_string_buffer(1 << 16)
+    rc = lib.flex_ceilings_run(buf, len(buf), what, reps)
+    text = buf.value.decode()
+    return json.loads(text) if rc == 0 else {"error": text}
+
+
+def kernel_sources_hash():
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profiles():
+    """HBM bytes per launch of the reduce kernel from the committed rocprofv3
+    counter summary (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel
+    calibration).  The summary names the kernel sources it was measured on; if
+    they have changed since, the figure is stale and None is returned."""
+    note = {"source": PMC_SUMMARY, "kernel_sources": kernel_sources_hash()}
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1].strip())
-    except OSError:
-        pass
-    return None
+        fields = {}
+        for line in open(os.path.join(ROOT, PMC_SUMMARY)):
+            if ":" in line and not line.startswith(" "):
+                k, v = line.split(":", 1)
+                fields[k.strip()] = v.strip()
+        measured_on = fields.get("kernel_sources_sha256", "")
+        note["measured_on_kernel_sources"] = measured_on
+        if measured_on == note["kernel_sources"]:
+            return float(fields["traffic_bytes_per_launch"]), note
+        note["stale"] = True
+    except (OSError, KeyError, ValueError):
+        note["missing"] = True
+    return None, note
 
 
 def cpu_baseline(oc, ar_host, ag_host, ar_bytes, ag_bytes, budget_s=10.0):
@@ -109,20 +162,16 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only launch a plain copy of known size (1-rank AllGather of 1 GiB, 10 launches): the "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--no-extras", action="store_true", help="skip the untimed warm / static-split legs")
-    ap.add_argument("--event-every", type=int, default=4,
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed warm / static-split / ceilings legs")
+    ap.add_argument("--event-every", type=int, default=0,
                     help="bracket the two calls of every K-th timed step with HIP events (per-kernel times for the "
-                         "roofline); the event packets themselves cost a few microseconds of stream time each")
-    ap.add_argument("--reduce-threads", type=int, default=0)
-    ap.add_argument("--reduce-unroll", type=int, default=0)
-    ap.add_argument("--reduce-waves", type=int, default=0)
-    ap.add_argument("--copy-threads", type=int, default=0)
-    ap.add_argument("--copy-unroll", type=int, default=0)
-    ap.add_argument("--copy-waves", type=int, default=0)
+                         "roofline); 0 = every step up to 50 steps, every 4th beyond")
+    ap.add_argument("--launch-shape", type=int, default=-1, help="0: 64-thread workgroups, 1: 256-thread workgroups")
     ap.add_argument("--reduce-nt", type=int, default=-1)
     ap.add_argument("--copy-nt", type=int, default=-1)
-    ap.add_argument("--reduce-serial", type=int, default=-1, help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
-    ap.add_argument("--host-engine", type=int, default=-1)
+    ap.add_argument("--reduce-serial", type=int, default=-1,
+                    help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
+    ap.add_argument("--host-engine", type=int, default=-1, help="0 hybrid, 1 copy kernels, 2 DMA engines")
     ap.add_argument("--host-blocks", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -148,7 +197,8 @@ def main():
         assert torch.equal(src.view(torch.int16), dst.view(torch.int16))
         fx.flex_comm_destroy(comm)
         print(json.dumps({"calibration": "gather_copy_kernel, 1 rank, 10 launches",
-                          "read_bytes_per_launch": 2 * n, "write_bytes_per_launch": 2 * n}))
+                          "read_bytes_per_launch": 2 * n, "write_bytes_per_launch": 2 * n,
+                          "kernel_sources_sha256": kernel_sources_hash()}))
         return
 
     w_ar, w_ag = wl.config(2), wl.config(1)
@@ -164,22 +214,16 @@ def main():
     ag_bytes = 2 * N * w_ag.bytes_per_rank
 
     cfg = fx.flex_config_default()
-    effective = {}
-    for key, val in (("reduce_threads", args.reduce_threads), ("reduce_unroll", args.reduce_unroll),
-                     ("reduce_waves_per_cu", args.reduce_waves), ("copy_threads", args.copy_threads),
-                     ("copy_unroll", args.copy_unroll), ("copy_waves_per_cu", args.copy_waves),
-                     ("host_blocks", args.host_blocks)):
-        if val:
-            setattr(cfg, key, val)
+    if args.host_blocks:
+        cfg.host_blocks = args.host_blocks
     for key, val in (("reduce_nontemporal", args.reduce_nt), ("copy_nontemporal", args.copy_nt),
-                     ("host_engine", args.host_engine), ("reduce_serial_loads", args.reduce_serial)):
+                     ("host_engine", args.host_engine), ("reduce_serial_loads", args.reduce_serial),
+                     ("launch_shape", args.launch_shape)):
         if val >= 0:
             setattr(cfg, key, val)
-    for key in ("reduce_threads", "reduce_serial_loads", "reduce_unroll", "reduce_waves_per_cu", "reduce_nontemporal",
-                "copy_threads",
-                "copy_unroll", "copy_waves_per_cu", "copy_nontemporal", "host_engine", "host_blocks",
-                "chunk_bytes", "num_slots", "pipeline_depth"):
-        effective[key] = getattr(cfg, key)
+    effective = {key: getattr(cfg, key) for key in (
+        "launch_shape", "reduce_serial_loads", "reduce_nontemporal", "copy_nontemporal", "host_engine", "host_blocks",
+        "host_die_shift", "chunk_bytes", "min_step_bytes", "num_slots")}
     comm = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -217,6 +261,9 @@ def main():
                               "initial_shares": list(res.initial_shares)[:2],
                               "balanced_shares": list(res.balanced_shares)[:2],
                               "balanced_split_ms": res.combined_s * 1e3, "device_alone_ms": res.device_alone_s * 1e3,
+                              "balanced_split_mad_ms": res.combined_mad_s * 1e3,
+                              "device_alone_mad_ms": res.device_alone_mad_s * 1e3,
+                              "acceptance_samples_each": res.accept_samples,
                               "reverted_to_device_only": bool(res.reverted),
                               "shares": list(res.shares)[:2], "iterations": res.iterations}
                 log("tuned", name, tune[name])
@@ -238,7 +285,7 @@ def main():
     s_ar0 = stats(fx.FLEX_ALLREDUCE, w_ar)
 
     # ---- timed region: exactly --steps steps --------------------------------
-    every = max(1, args.event_every)
+    every = args.event_every if args.event_every > 0 else (1 if args.steps <= 50 else 4)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(0, args.steps, every)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -273,17 +320,25 @@ def main():
     if split_samples > 0:
         total_dev_s = s_ar1.mean_time_s[0] * s_ar1.samples - s_ar0.mean_time_s[0] * s_ar0.samples
         kern_ms = total_dev_s / split_samples * 1e3
+        spread = {}
         how = "Evaluator events fork->device-path-done, mean of %d split calls" % split_samples
+        nlaunch = int(split_samples)
     else:
         kern_ms = sum(ar_ms) / len(ar_ms)
+        spread = {"launch_ms_p10": percentile(ar_ms, 0.1), "launch_ms_p90": percentile(ar_ms, 0.9)}
         how = ("HIP events on the launch stream around every %slaunch of the timed region, mean of %d launches"
                % ("" if every == 1 else "%d-th " % every, len(ar_ms)))
+        nlaunch = len(ar_ms)
     bytes_per_elem = (N + 1) * 2
     achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9
+    traffic, traffic_note = traffic_from_profiles()
     roofline = {"bound": "hbm", "kernel": "reduce_n_kernel<8, bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note(),
-                "launch_ms": kern_ms, "elements_per_launch": int(dev_elems), "bytes_per_element": bytes_per_elem,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_from_profiles": traffic_note,
+                "launch_ms": kern_ms, "launches_timed": nlaunch, "elements_per_launch": int(dev_elems),
+                "bytes_per_element": bytes_per_elem,
                 "algorithmic_bytes_per_launch": int(bytes_per_elem * dev_elems), "timing": how}
+    roofline.update(spread)
 
     def host_units(st):
         return int(st.balancer.shares[1]) if args.mode == "adaptive" else int(st.static_host_units)
@@ -299,10 +354,12 @@ def main():
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": roofline,
         "allreduce": {"ms_median": median(ar_ms), "ms_p10": percentile(ar_ms, 0.1), "ms_p90": percentile(ar_ms, 0.9),
+                      "calls_timed": len(ar_ms),
                       "hbm_GBs": ar_bytes / (median(ar_ms) * 1e-3) / 1e9,
                       "algbw_GBs": w_ar.bytes_per_rank / (median(ar_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ar1), "split_calls_timed": int(split_samples)},
         "allgather": {"ms_median": median(ag_ms), "ms_p10": percentile(ag_ms, 0.1), "ms_p90": percentile(ag_ms, 0.9),
+                      "calls_timed": len(ag_ms),
                       "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
                       "algbw_GBs": N * w_ag.bytes_per_rank / (median(ag_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ag1)},
@@ -321,8 +378,8 @@ def main():
             extras[name] = {"allreduce_ms": d_ar, "allreduce_hbm_GBs": ar_bytes / d_ar / 1e6,
                             "allgather_ms": d_ag, "allgather_hbm_GBs": ag_bytes / d_ag / 1e6}
         extras["warm_same_buffers"]["note"] = ("same buffers every call, library defaults (non-temporal stores "
-                                               "do not linger in the Infinity Cache, so this is close to cold)")
-        # plain (write-back) stores let a reused 256 MiB output stay resident in the 256 MB Infinity Cache:
+                                               "do not linger in the memory-side cache, so this is close to cold)")
+        # plain (write-back) stores let a reused 256 MiB output stay resident in the 256 MB memory-side cache:
         # HBM then sees fewer bytes than the algorithm moves
         cfg2 = fx.flex_config_default()
         cfg2.reduce_nontemporal = 1
@@ -338,7 +395,7 @@ def main():
         d = median([a.elapsed_time(b) for a, b in evs])
         extras["warm_same_buffers_plain_stores"] = {
             "allreduce_ms": d, "allreduce_hbm_GBs": ar_bytes / d / 1e6,
-            "note": "reduce_nontemporal = 1: the reused output stays in the Infinity Cache, its stores never reach HBM"}
+            "note": "reduce_nontemporal = 1: the reused output stays in the memory-side cache, its stores never reach HBM"}
         # configuration 2's static split sweep: device-only vs 5 / 12 / 22 % through pinned host memory
         sweep = {}
         for units in (0, 100, 500, 1200, 2200):
@@ -360,7 +417,17 @@ def main():
                             "host_path_ms": t_host * 1e3, "pcie_GBs_per_direction": pcie,
                             "pcie_frac_of_64GBs": pcie / PCIE_PEAK_GBS})
             sweep[str(units)] = row
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 0)
         extras["allreduce_static_split"] = sweep
+        result["host_path"] = {
+            "workload": "configs[2]: 8 x 256 MiB bf16 AllReduce, static host share, 7 peers' parts each way",
+            "peak_GBs_per_direction": PCIE_PEAK_GBS, "engine": int(cfg.host_engine),
+            "pcie_GBs_per_direction": {"%g%%" % (u / 100.0): sweep[str(u)].get("pcie_GBs_per_direction")
+                                       for u in (500, 1200, 2200)},
+            "allreduce_ms": {"%g%%" % (u / 100.0): sweep[str(u)]["allreduce_ms"] for u in (0, 500, 1200, 2200)}}
+        torch.cuda.synchronize()
+        log("measuring this box's ceilings ...")
+        extras["ceilings"] = measure_ceilings()
         result["extras"] = extras
 
     if not args.no_cpu_baseline:

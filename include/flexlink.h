@@ -95,6 +95,11 @@ typedef struct flex_balancer_cfg {
     uint32_t max_tune_iters;       /* Algorithm 1 loop bound (paper: 100) */
     uint32_t window;               /* Stage 2: calls per Evaluator window = Load Balancer period (default 10) */
     uint32_t runtime_step;         /* Stage 2: fixed share moved per adjustment, in units (default 4) */
+    uint32_t aux_share_cap;        /* 0 = none (the paper's method unchanged); else no auxiliary path is ever
+                                      filled beyond this many units: a transfer is trimmed to the room left,
+                                      and a transfer trimmed to nothing leaves the shares alone (Stage 1 counts
+                                      such an iteration as a stable one) */
+    uint32_t reserved;
     double convergence_threshold;  /* Algorithm 1 CONVERGENCE_THRESHOLD on (Tslow-Tfast)/Tfast (default 0.05) */
     double runtime_threshold;      /* Stage 2 threshold on the same ratio of window medians (default 0.10) */
 } flex_balancer_cfg_t;
@@ -116,7 +121,8 @@ typedef struct flex_balancer_state {
 int flex_balancer_cfg_default(flex_balancer_cfg_t* cfg);
 
 /* Create a balancer in Stage 1 with bandwidth-proportional starting shares
- * (the paper's InitializeShares, "NVLink gets dominant share").
+ * (Algorithm 1's InitializeShares step: the primary path starts with the
+ * largest share).
  *   b        host pointer; receives the new object (caller destroys it).
  *   npaths   1..FLEX_MAX_PATHS.
  *   path_bw  host array of npaths rates, same unit for all: how fast path p
@@ -155,10 +161,10 @@ int flex_balancer_update(flex_balancer_t* b, const double* path_time_s, uint32_t
 int flex_balancer_finish_tuning(flex_balancer_t* b);
 
 /* Give every auxiliary path's share back to the primary path, deactivate them
- * and end Stage 1: the state Algorithm 1 itself ends in when "only NVLink
- * remains".  Used when the split, however balanced, is no faster than the
- * primary path alone (paper, Section "Two-Stage Load Balancing Strategy": the
- * system then reverts to the primary-only baseline). */
+ * and end Stage 1: the state Algorithm 1 itself ends in once the primary path
+ * is the only active one.  Used when the split, however balanced, is no faster
+ * than the primary path alone (paper, Section "Two-Stage Load Balancing
+ * Strategy": the system then falls back to the primary-only baseline). */
 int flex_balancer_revert_to_primary(flex_balancer_t* b);
 
 /* Copy the balancer's state to *out (host pointer). */
@@ -203,11 +209,18 @@ int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint
  * Communicator (paper: Section "Communicator").
  * ---------------------------------------------------------------------- */
 enum flex_host_engine {
-    FLEX_ENGINE_KERNEL = 0, /* both stages of the host path are small HIP kernels that write to / read
-                               from the pinned buffer over PCIe; for AllReduce the second stage is the
-                               reduce kernel itself, reading the peers straight from pinned memory */
-    FLEX_ENGINE_SDMA = 1    /* both stages are hipMemcpyAsync copies (DMA engines); AllReduce then
-                               reduces from a device scratch buffer */
+    FLEX_ENGINE_HYBRID = 0, /* default.  Producer stage: one small copy kernel writes all peers' pieces into
+                               the pinned slot over PCIe; consumer stage: one hipMemcpyAsync (DMA engine)
+                               brings the slot back into a device staging buffer, and a kernel on a third
+                               stream reduces from there (AllReduce) or places the pieces (AllGather).
+                               On MI355X this is the pairing that keeps both PCIe directions busy: a DMA
+                               engine writes host memory at half the rate of a copy kernel, and a kernel
+                               reading host memory is starved by the producer's writes. */
+    FLEX_ENGINE_KERNEL = 1, /* both stages are small HIP kernels that write to / read from the pinned buffer
+                               over PCIe; for AllReduce the second stage is the reduce kernel itself, reading
+                               the peers straight from pinned memory */
+    FLEX_ENGINE_SDMA = 2    /* both stages are hipMemcpyAsync copies (DMA engines), one per peer and step;
+                               AllReduce then reduces once from a device scratch buffer */
 };
 
 enum flex_slot_sync {
@@ -218,48 +231,55 @@ enum flex_slot_sync {
                                the consumer waits semFull >= i+1, drains it, writes semEmpty = i+1 */
 };
 
+enum flex_launch_shape {
+    FLEX_SHAPE_WAVE = 0,    /* default: one wavefront (64 threads) per workgroup, one workgroup per 1 KiB
+                               tile of each input; best or within 2 % at every size measured on MI355X */
+    FLEX_SHAPE_BLOCK = 1    /* 256-thread workgroups, one per 4 KiB tile: the one alternate that wins
+                               anywhere (about 10 % on AllReduce messages around 2 MiB per rank) */
+};
+
 typedef struct flex_config {
+    uint32_t struct_size;        /* sizeof(flex_config_t) as the caller's header declares it.
+                                    flex_config_default() fills it in; flex_comm_create() refuses any other
+                                    value, so a caller built against another layout fails loudly */
+    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering */
     uint64_t chunk_bytes;        /* transit buffer bytes per peer and pipeline step (paper: 4 MB; default
                                     4 MiB); one pinned slot holds (nranks-1) * chunk_bytes */
-    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering */
-    uint32_t max_host_units;     /* largest host share a call may use; sizes the device scratch
-                                    (default 2500 = 25 %) */
-    uint32_t split_align_elems;  /* alignment of the cut, elements (default 2048) */
     uint64_t min_split_bytes;    /* messages shorter than this per rank are never split (default 64 KiB) */
+    uint32_t max_host_units;     /* largest share one host path may carry (default 2500 = 25 %); sizes the
+                                    FLEX_ENGINE_SDMA scratch and is the balancers' aux_share_cap */
+    uint32_t split_align_elems;  /* alignment of the cut, elements (default 2048) */
     uint32_t tune_reps;          /* collective calls per MeasurePathTimings in flex_comm_tune (default 5) */
     uint32_t probe_units;        /* host share used to measure the host path's rate (default 200) */
-    /* launch shapes of the two kernels; 0 = library default */
-    uint32_t reduce_threads;     /* workgroup size of the N-way reduce kernel (64..1024, multiple of 64) */
-    uint32_t reduce_unroll;      /* 16-byte vectors per thread per input per tile: 1, 2 or 4 (used when
-                                    reduce_serial_loads = 0) */
-    uint32_t reduce_waves_per_cu;/* 0 = one workgroup per tile; else a persistent grid sized to this many
-                                    wavefronts per compute unit, striding over tiles */
-    uint32_t copy_threads;
-    uint32_t copy_unroll;        /* 1, 2, 4 or 8 */
-    uint32_t copy_waves_per_cu;
-    uint32_t reduce_nontemporal; /* streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores */
+    uint32_t tune_accept_check;  /* 1 (default): flex_comm_tune keeps the tuned split only if it is faster
+                                    than the device path alone by a margin the noise cannot explain */
+    uint32_t accept_pairs;       /* acceptance check: interleaved (split, device-only) measurement pairs of
+                                    tune_reps calls each (default 3, at least 1) */
+    uint32_t launch_shape;       /* flex_launch_shape of the two device-path kernels */
+    uint32_t reduce_serial_loads;/* device-path reduce kernel.  2 = a wavefront keeps one load in flight and asks
+                                    for input r+1 only when input r has arrived; 0 = all N loads of a tile are
+                                    issued before the first add; 1 (default) = the first for launches of at
+                                    least 16 tiles per compute unit (4 MiB of bf16 per rank on MI355X), the
+                                    second for shorter ones */
+    uint32_t reduce_nontemporal; /* streaming hints of the reduce kernel: 0 none, 1 non-temporal loads,
+                                    3 (default) non-temporal loads and stores.  Plain stores let a reused
+                                    output stay in the 256 MB memory-side cache (an nccl-tests style loop) */
     uint32_t copy_nontemporal;   /* same for the copy kernel */
-    uint32_t host_engine;        /* flex_host_engine (default FLEX_ENGINE_KERNEL) */
-    uint32_t host_blocks;        /* FLEX_ENGINE_KERNEL: workgroups (of 256 threads) each host-path kernel may
-                                    occupy (default 16) */
-    uint32_t pipeline_depth;     /* a host part shorter than pipeline_depth * chunk_bytes per peer is still
-                                    cut into up to this many steps so that the two stages overlap (default 4) */
-    uint32_t min_step_bytes;     /* ... but no step is shorter than this per peer (default 256 KiB) */
-    uint32_t tune_accept_check;  /* 1 (default): flex_comm_tune keeps the tuned split only if it finishes
-                                    sooner than the device path alone, else reverts to device-only */
+    uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_HYBRID; the
+                                    benchmark target's hipMemcpyAsync-both-ways engine is FLEX_ENGINE_SDMA) */
+    uint32_t host_blocks;        /* workgroups (of 256 threads) each host-path kernel that touches pinned
+                                    memory may occupy (default 8: two already fill the link) */
+    uint32_t host_die_shift;     /* 0 = host-path workgroups spread over all 8 accelerator dies; 1..3 = their
+                                    grids are 2^shift times larger and only every 2^shift-th workgroup works,
+                                    which keeps them on 4, 2 (default) or 1 of the dies and disturbs the device
+                                    path less */
+    uint32_t min_step_bytes;     /* shortest pipeline step per peer (default 256 KiB): a host part starts and
+                                    ends with steps of this size, doubling up to chunk_bytes in between, so
+                                    that little of it travels with only one of the two stages busy */
     uint32_t slot_sync;          /* flex_slot_sync (default FLEX_SYNC_EVENTS) */
     uint32_t num_aux_paths;      /* host-staged paths: 1 (default) = FLEX_PATH_HOST with host_engine;
-                                    2 = also FLEX_PATH_HOST2 with the other engine */
-    uint32_t host_die_shift;     /* FLEX_ENGINE_KERNEL: 0 = host-path workgroups spread over all 8 accelerator
-                                    dies; 1..3 = their grids are 2^shift times larger and only every 2^shift-th
-                                    workgroup works, which keeps them on 4, 2 (default) or 1 of the dies and
-                                    disturbs the device path less */
-    uint32_t reduce_serial_loads;/* device-path reduce kernel.  2 = a wavefront keeps one load in flight and asks
-                                    for input r+1 only when input r has arrived; 0 = all N * reduce_unroll
-                                    loads of a tile are issued before the first add; 1 (default) = the first
-                                    for launches of at least 16 tiles per compute unit (4 MiB of bf16 per
-                                    rank on MI355X), the second for shorter ones */
-    uint32_t reserved;
+                                    2 = also FLEX_PATH_HOST2 with the next engine in the enum's cyclic order */
+    uint32_t reserved[2];
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 
@@ -286,16 +306,29 @@ typedef struct flex_stats {
 typedef struct flex_tune_result {
     double path_bw[FLEX_MAX_PATHS];         /* measured rates, message bytes per second */
     uint32_t initial_shares[FLEX_MAX_PATHS];/* InitializeShares' result */
-    uint32_t shares[FLEX_MAX_PATHS];        /* shares after Algorithm 1 */
+    uint32_t shares[FLEX_MAX_PATHS];        /* shares after Algorithm 1 and the acceptance check */
     uint32_t active_mask;
     uint32_t iterations;                    /* Algorithm 1 iterations measured */
     double path_time_s[FLEX_MAX_PATHS];     /* last measured per-path times */
     uint32_t balanced_shares[FLEX_MAX_PATHS]; /* shares Algorithm 1 ended with, before the acceptance check */
-    double device_alone_s;                  /* whole message on the device path alone (median) */
-    double combined_s;                      /* slowest path's time at balanced_shares (median); 0 if not measured */
-    uint32_t reverted;                      /* 1 = the acceptance check reverted to device-only */
-    uint32_t reserved;
+    /* acceptance check (all 0 if it did not run): whole-call times, events around the call on the
+       caller's stream, accept_pairs * tune_reps samples of each kind taken in turns */
+    double device_alone_s;                  /* median, whole message on the device path */
+    double combined_s;                      /* median, call split at balanced_shares */
+    double device_alone_mad_s;              /* median absolute deviation of the device-only samples */
+    double combined_mad_s;                  /* same for the split samples */
+    uint32_t accept_samples;                /* samples of each kind */
+    uint32_t reverted;                      /* 1 = not faster by more than 3 * max(MAD): reverted to device-only */
 } flex_tune_result_t;
+
+/* One iteration of Algorithm 1 as flex_comm_tune ran it. */
+typedef struct flex_tune_round {
+    double path_time_s[FLEX_MAX_PATHS];      /* MeasurePathTimings' result (0 for inactive paths) */
+    uint32_t shares_before[FLEX_MAX_PATHS];  /* shares the measurement was taken at */
+    uint32_t shares_after[FLEX_MAX_PATHS];   /* shares after the iteration's move */
+    uint32_t step_after;
+    uint32_t active_after;                   /* bit p = path p still active */
+} flex_tune_round_t;
 
 /* Fill *cfg (host pointer) with defaults. */
 int flex_config_default(flex_config_t* cfg);
@@ -307,12 +340,14 @@ int flex_config_default(flex_config_t* cfg);
  *                       buffer is local and never takes the host path.
  *   max_bytes_per_rank  largest per-rank message any later call will pass.
  *   cfg                 host pointer or NULL for defaults.
- * Allocates, once: num_slots pinned slots of (nranks-1) * chunk_bytes, two side
- * streams at default priority, an event ring and, for FLEX_ENGINE_SDMA only, a
- * device scratch of (nranks-1) * ceil(max_bytes_per_rank * max_host_units /
- * share_total) bytes (rounded up).
- * Nothing is allocated per call afterwards.
- * Errors: INVALID_ARG, NOMEM, HIP. */
+ * Allocates, once, per host path: num_slots pinned slots of (nranks-1) *
+ * chunk_bytes, three side streams at default priority, slot events and, by
+ * engine, device memory: FLEX_ENGINE_HYBRID num_slots staging buffers of the
+ * slot size; FLEX_ENGINE_SDMA a scratch of (nranks-1) * ceil(max_bytes_per_rank
+ * * max_host_units / share_total) bytes (rounded up); FLEX_ENGINE_KERNEL none.
+ * Plus one ring of timing events.  Nothing is allocated per call afterwards.
+ * Errors: INVALID_ARG (also cfg->struct_size != sizeof(flex_config_t)), NOMEM,
+ * HIP. */
 int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_per_rank,
                      const flex_config_t* cfg);
 
@@ -417,9 +452,11 @@ int flex_set_split_paths(flex_comm_t* comm, int coll, int mode, const uint32_t* 
  * each host path at probe_units with the other idle), then Algorithm 1 with MeasurePathTimings = median
  * of tune_reps calls, until the balancer leaves Stage 1.  Then, unless
  * tune_accept_check is 0 or the host path was already drained, the balanced
- * split is timed once more against the device path alone and reverted to
- * device-only if it is not faster (the two paths share the GPU's memory
- * system, so a balanced split can be slower than no split).  The resulting
+ * split is timed against the device path alone, accept_pairs times in turns
+ * (split, device-only, split, ...), and kept only if its median is lower by
+ * more than three times the larger median absolute deviation; otherwise the
+ * class reverts to device-only (the two paths share the GPU's memory system,
+ * so a balanced split can be slower than no split).  The resulting
  * balancer is stored for the message's size class (replacing an older one).
  * Arguments as for the collective itself; `out` is overwritten with the
  * collective's (correct) result.  result may be NULL.
@@ -449,10 +486,33 @@ int flex_evaluator_drain(flex_comm_t* comm);
  * `count` elements of `dtype`.  out: host pointer. */
 int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_stats_t* out);
 
+/* The iterations of the last flex_comm_tune for the size class of a message of
+ * `count` elements of `dtype`, oldest first: up to max_rounds entries are
+ * written to rounds (host array), *nrounds receives how many the tuning ran
+ * (it may exceed max_rounds; at most 128 are kept).
+ * Errors: INVALID_ARG (null, unknown collective), UNSUPPORTED (dtype),
+ * STATE (that class was never tuned). */
+int flex_comm_tune_trace(flex_comm_t* comm, int coll, size_t count, int dtype, flex_tune_round_t* rounds,
+                         uint32_t max_rounds, uint32_t* nrounds);
+
+/* How a host part of `bytes` bytes per peer is cut into pipeline steps (paper:
+ * Section "Communicator", the double-buffered PD2H / H2CD pipeline): step sizes
+ * start at min_step_bytes, double up to chunk_bytes, stay there, and halve back
+ * down to min_step_bytes at the end, so that the stretch at either end of the
+ * transfer where only one of the two stages is busy is short.  Every step is a
+ * multiple of 256 bytes except that the last one also takes what is left over;
+ * no step exceeds chunk_bytes.  Pure host arithmetic.
+ *   steps   host array receiving up to max_steps sizes (may be NULL to count);
+ *   nsteps  receives the number of steps of the plan.
+ * Errors: INVALID_ARG (null nsteps, chunk_bytes < 512 or not a multiple of 256,
+ * min_step_bytes == 0). */
+int flex_pipeline_plan(uint64_t bytes, uint64_t chunk_bytes, uint64_t min_step_bytes, uint64_t* steps,
+                       uint32_t max_steps, uint32_t* nsteps);
+
 /* sizeof() of the structs of this header as the library was compiled, for
- * bindings that mirror them: out[0..4] = flex_balancer_cfg_t,
- * flex_balancer_state_t, flex_config_t, flex_stats_t, flex_tune_result_t.
- * out: host array of 5.  Errors: INVALID_ARG (null). */
+ * bindings that mirror them: out[0..5] = flex_balancer_cfg_t,
+ * flex_balancer_state_t, flex_config_t, flex_stats_t, flex_tune_result_t,
+ * flex_tune_round_t.  out: host array of 6.  Errors: INVALID_ARG (null). */
 int flex_struct_sizes(size_t* out);
 
 /* Static strings; never NULL. */

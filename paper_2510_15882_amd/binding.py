@@ -21,7 +21,8 @@ FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER, FLEX_ALLTOALL = 0, 1, 2, 3
 FLEX_PATH_DEVICE, FLEX_PATH_HOST, FLEX_PATH_HOST2 = 0, 1, 2
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
-FLEX_ENGINE_KERNEL, FLEX_ENGINE_SDMA = 0, 1
+FLEX_ENGINE_HYBRID, FLEX_ENGINE_KERNEL, FLEX_ENGINE_SDMA = 0, 1, 2
+FLEX_SHAPE_WAVE, FLEX_SHAPE_BLOCK = 0, 1
 FLEX_SYNC_EVENTS, FLEX_SYNC_COUNTERS = 0, 1
 
 u32, u64, i32, f64 = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double
@@ -43,6 +44,7 @@ class _Struct(ctypes.Structure):
 class BalancerCfg(_Struct):
     _fields_ = [("share_total", u32), ("initial_step", u32), ("stability_required", u32),
                 ("max_tune_iters", u32), ("window", u32), ("runtime_step", u32),
+                ("aux_share_cap", u32), ("reserved", u32),
                 ("convergence_threshold", f64), ("runtime_threshold", f64)]
 
 
@@ -53,13 +55,12 @@ class BalancerState(_Struct):
 
 
 class Config(_Struct):
-    _fields_ = [("chunk_bytes", u64), ("num_slots", u32), ("max_host_units", u32),
-                ("split_align_elems", u32), ("min_split_bytes", u64), ("tune_reps", u32),
-                ("probe_units", u32), ("reduce_threads", u32), ("reduce_unroll", u32),
-                ("reduce_waves_per_cu", u32), ("copy_threads", u32), ("copy_unroll", u32),
-                ("copy_waves_per_cu", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
-                ("host_engine", u32), ("host_blocks", u32), ("pipeline_depth", u32), ("min_step_bytes", u32),
-                ("tune_accept_check", u32), ("slot_sync", u32), ("num_aux_paths", u32), ("host_die_shift", u32), ("reduce_serial_loads", u32), ("reserved", u32),
+    _fields_ = [("struct_size", u32), ("num_slots", u32), ("chunk_bytes", u64), ("min_split_bytes", u64),
+                ("max_host_units", u32), ("split_align_elems", u32), ("tune_reps", u32), ("probe_units", u32),
+                ("tune_accept_check", u32), ("accept_pairs", u32), ("launch_shape", u32),
+                ("reduce_serial_loads", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
+                ("host_engine", u32), ("host_blocks", u32), ("host_die_shift", u32), ("min_step_bytes", u32),
+                ("slot_sync", u32), ("num_aux_paths", u32), ("reserved", u32 * 2),
                 ("balancer", BalancerCfg)]
 
 
@@ -76,7 +77,13 @@ class TuneResult(_Struct):
     _fields_ = [("path_bw", f64 * FLEX_MAX_PATHS), ("initial_shares", u32 * FLEX_MAX_PATHS),
                 ("shares", u32 * FLEX_MAX_PATHS), ("active_mask", u32), ("iterations", u32),
                 ("path_time_s", f64 * FLEX_MAX_PATHS), ("balanced_shares", u32 * FLEX_MAX_PATHS),
-                ("device_alone_s", f64), ("combined_s", f64), ("reverted", u32), ("reserved", u32)]
+                ("device_alone_s", f64), ("combined_s", f64), ("device_alone_mad_s", f64),
+                ("combined_mad_s", f64), ("accept_samples", u32), ("reverted", u32)]
+
+
+class TuneRound(_Struct):
+    _fields_ = [("path_time_s", f64 * FLEX_MAX_PATHS), ("shares_before", u32 * FLEX_MAX_PATHS),
+                ("shares_after", u32 * FLEX_MAX_PATHS), ("step_after", u32), ("active_after", u32)]
 
 
 class FlexError(RuntimeError):
@@ -126,6 +133,8 @@ def lib():
         "flex_set_split": [vp, ci, ci, u32],
         "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
         "flex_comm_set_shares": [vp, ci, sz, ci, P(u32)],
+        "flex_comm_tune_trace": [vp, ci, sz, ci, P(TuneRound), u32, P(u32)],
+        "flex_pipeline_plan": [u64, u64, u64, P(u64), u32, P(u32)],
         "flex_evaluator_poll": [vp],
         "flex_evaluator_drain": [vp],
         "flex_get_stats": [vp, ci, sz, ci, P(Stats)],
@@ -208,7 +217,7 @@ def flex_balancer_destroy(b):
 
 
 def flex_struct_sizes():
-    out = (ctypes.c_size_t * 5)()
+    out = (ctypes.c_size_t * 6)()
     _check(lib().flex_struct_sizes(out))
     return list(out)
 
@@ -330,6 +339,22 @@ def flex_set_split_paths(comm, coll, mode, aux_units=()):
 def flex_comm_set_shares(comm, coll, count, dtype, shares):
     arr = (u32 * FLEX_MAX_PATHS)(*shares)
     _check(lib().flex_comm_set_shares(comm, coll, count, dtype_code(dtype), arr))
+
+
+def flex_comm_tune_trace(comm, coll, count, dtype, max_rounds=128):
+    """The iterations of the last flex_comm_tune of that size class (list of TuneRound) and how many it ran."""
+    arr = (TuneRound * max_rounds)()
+    n = u32()
+    _check(lib().flex_comm_tune_trace(comm, coll, count, dtype_code(dtype), arr, max_rounds, ctypes.byref(n)))
+    return [arr[k] for k in range(min(n.value, max_rounds))], n.value
+
+
+def flex_pipeline_plan(nbytes, chunk_bytes=4 << 20, min_step_bytes=256 << 10):
+    n = u32()
+    _check(lib().flex_pipeline_plan(nbytes, chunk_bytes, min_step_bytes, None, 0, ctypes.byref(n)))
+    arr = (u64 * max(n.value, 1))()
+    _check(lib().flex_pipeline_plan(nbytes, chunk_bytes, min_step_bytes, arr, n.value, ctypes.byref(n)))
+    return list(arr)[:n.value]
 
 
 def flex_evaluator_poll(comm):

@@ -16,6 +16,8 @@ void balancer_cfg_default(flex_balancer_cfg_t* c) {
     c->max_tune_iters = 100;
     c->window = 10;
     c->runtime_step = 4;
+    c->aux_share_cap = 0;
+    c->reserved = 0;
     c->convergence_threshold = 0.05;
     c->runtime_threshold = 0.10;
 }
@@ -93,13 +95,19 @@ void Balancer::slowest_fastest(const double* T, int* slow, int* fast) const {
 
 // One share transfer with the primary-first rule shared by both stages: the
 // slowest path gives; the primary receives unless it is itself the slowest (or
-// inactive), in which case the fastest path receives.
-void Balancer::move_share(int slow, int fast, uint32_t amount) {
+// inactive), in which case the fastest path receives.  An auxiliary receiver
+// is never filled beyond cfg.aux_share_cap (0 = no ceiling).
+uint32_t Balancer::move_share(int slow, int fast, uint32_t amount) {
     int target = (slow != 0 && (active_mask & 1u)) ? 0 : fast;
     uint32_t m = std::min(amount, shares[slow]);
+    if (target != 0 && cfg.aux_share_cap > 0) {
+        uint32_t room = shares[target] < cfg.aux_share_cap ? cfg.aux_share_cap - shares[target] : 0;
+        m = std::min(m, room);
+    }
     shares[slow] -= m;
     shares[target] += m;
     if (shares[slow] == 0) active_mask &= ~(1u << slow);
+    return m;
 }
 
 bool Balancer::times_ok(const double* T) const {
@@ -120,9 +128,14 @@ bool Balancer::update(const double* T) {
             ++stability_count;
             stable = stability_count >= cfg.stability_required;
         } else {
+            const uint32_t calm_before = stability_count;
             stability_count = 0;
             if (prev_slowest >= 0 && slow != prev_slowest) step = std::max(step / 2, 1u);
-            move_share(slow, fast, step);
+            if (move_share(slow, fast, step) == 0) {
+                // the receiver sits at its ceiling: nothing can change any more
+                stability_count = calm_before + 1;
+                stable = stability_count >= cfg.stability_required;
+            }
             prev_slowest = slow;
         }
         end_tuning_if_done(stable);
@@ -149,10 +162,7 @@ bool Balancer::update(const double* T) {
     int slow, fast;
     slowest_fastest(med, &slow, &fast);
     double gap = (med[slow] - med[fast]) / med[fast];
-    if (gap > cfg.runtime_threshold) {
-        move_share(slow, fast, cfg.runtime_step);
-        ++adjustments;
-    }
+    if (gap > cfg.runtime_threshold && move_share(slow, fast, cfg.runtime_step) > 0) ++adjustments;
     return true;
 }
 
@@ -282,6 +292,7 @@ int flex_struct_sizes(size_t* out) {
     out[2] = sizeof(flex_config_t);
     out[3] = sizeof(flex_stats_t);
     out[4] = sizeof(flex_tune_result_t);
+    out[5] = sizeof(flex_tune_round_t);
     return FLEX_OK;
 }
 
@@ -302,6 +313,16 @@ int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint
     if (sum > share_total)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_partition_paths: shares exceed share_total");
     flex::partition_paths(count, units, npaths, share_total, align_elems, min_count, start_out);
+    return FLEX_OK;
+}
+
+int flex_pipeline_plan(uint64_t bytes, uint64_t chunk_bytes, uint64_t min_step_bytes, uint64_t* steps,
+                       uint32_t max_steps, uint32_t* nsteps) {
+    if (!nsteps || chunk_bytes < 512 || chunk_bytes % 256 || min_step_bytes == 0)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_pipeline_plan: argument out of range");
+    const std::vector<uint64_t> plan = flex::plan_steps(bytes, chunk_bytes, min_step_bytes);
+    *nsteps = (uint32_t)plan.size();
+    for (size_t k = 0; steps && k < plan.size() && k < max_steps; ++k) steps[k] = plan[k];
     return FLEX_OK;
 }
 

@@ -14,6 +14,7 @@
 #include <new>
 #include <vector>
 
+#include "evaluator_ring.h"
 #include "flexlink_internal.h"
 
 namespace flex {
@@ -47,24 +48,39 @@ int fail(int status, const char* fmt, ...) {
 
 namespace {
 
-constexpr size_t kRingSize = 256;  // timing records that may be in flight
+constexpr size_t kRingSize = 256;    // timing records that may be in flight
+constexpr size_t kMaxTuneRounds = 128;  // iterations of Algorithm 1 kept for flex_comm_tune_trace
 constexpr int kMaxAux = FLEX_MAX_PATHS - 1;
 
-// One split call's events; the Evaluator reads the elapsed times back later.
-struct TimingRecord {
-    hipEvent_t fork = nullptr;
-    hipEvent_t done[FLEX_MAX_PATHS] = {nullptr, nullptr, nullptr, nullptr};
-    uint32_t used_mask = 0;  // bit p: path p carried part of the message
-    int coll = 0;
-    int size_class = 0;
-    bool adaptive = false;
-    uint64_t generation = 0;  // balancer generation the call's shares came from
+// The Evaluator's three event operations on the HIP runtime.
+struct HipEventApi {
+    int query(hipEvent_t e) {
+        hipError_t q = hipEventQuery(e);
+        if (q == hipSuccess) return 0;
+        if (q == hipErrorNotReady) return 1;
+        return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
+    }
+    int wait(hipEvent_t e) {
+        hipError_t q = hipEventSynchronize(e);
+        return q == hipSuccess ? 0 : flex::fail(FLEX_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(q));
+    }
+    int elapsed(hipEvent_t a, hipEvent_t b, double* seconds) {
+        float ms = 0.f;
+        hipError_t q = hipEventElapsedTime(&ms, a, b);
+        if (q != hipSuccess) return flex::fail(FLEX_ERR_HIP, "hipEventElapsedTime failed: %s", hipGetErrorString(q));
+        *seconds = ms * 1e-3;
+        return 0;
+    }
 };
+using Ring = flex::EvaluatorRing<hipEvent_t, HipEventApi>;
+using TimingRecord = Ring::Record;
 
 struct SizeClass {
     flex::Balancer bal;
     bool tuned = false;       // produced by flex_comm_tune / flex_comm_set_shares (else borrowed)
     uint64_t generation = 0;  // bumped whenever the shares change
+    std::vector<flex_tune_round_t> rounds;  // Algorithm 1 as flex_comm_tune ran it
+    uint32_t rounds_run = 0;
 };
 
 struct CollState {
@@ -88,9 +104,18 @@ int size_class_of(size_t bytes) {
 }
 
 double median_of(std::vector<double> v) {
+    if (v.empty()) return 0.0;
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
     return (n & 1) ? v[n / 2] : (v[n / 2 - 1] + v[n / 2]) / 2.0;
+}
+
+// median absolute deviation
+double mad_of(const std::vector<double>& v) {
+    const double m = median_of(v);
+    std::vector<double> d;
+    for (double x : v) d.push_back(std::fabs(x - m));
+    return median_of(d);
 }
 
 // What the consumer stage of a host path does with a step once it sits in the
@@ -110,12 +135,17 @@ struct HostJob {
 };
 
 // One host-staged path: a ring of pinned slots, a producer and a consumer
-// stream, and the slot hand-over state.
+// stream (plus, for the hybrid engine, a third one for the kernels that finish
+// a step out of the device staging buffers), and the slot hand-over state.
 struct HostPath {
-    int engine = FLEX_ENGINE_KERNEL;
-    hipStream_t s_up = nullptr, s_down = nullptr;  // producer / consumer stage
+    int engine = FLEX_ENGINE_HYBRID;
+    hipStream_t s_up = nullptr, s_down = nullptr, s_fin = nullptr;
     std::vector<void*> pinned;
     std::vector<hipEvent_t> ev_full, ev_empty;
+    // hybrid engine: one device staging buffer per slot, filled by the DMA
+    // engine and drained by a kernel on s_fin
+    std::vector<char*> stage;
+    std::vector<hipEvent_t> ev_staged, ev_stage_free;
     // FLEX_SYNC_COUNTERS: one pair of 64-bit counters per slot (signal memory) and
     // how often each slot has been used so far
     std::vector<uint64_t*> sem_full, sem_empty;
@@ -124,17 +154,25 @@ struct HostPath {
     char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
     size_t scratch_stride = 0;
 
-    void destroy() {
+    hipStream_t last_stream() const { return engine == FLEX_ENGINE_HYBRID ? s_fin : s_down; }
+
+    void quiesce() {
         if (s_up) (void)hipStreamSynchronize(s_up);
         if (s_down) (void)hipStreamSynchronize(s_down);
-        for (auto e : ev_full) (void)hipEventDestroy(e);
-        for (auto e : ev_empty) (void)hipEventDestroy(e);
+        if (s_fin) (void)hipStreamSynchronize(s_fin);
+    }
+
+    void destroy() {
+        quiesce();
+        for (auto* vec : {&ev_full, &ev_empty, &ev_staged, &ev_stage_free})
+            for (auto e : *vec) (void)hipEventDestroy(e);
         for (auto p : sem_full) (void)hipFree(p);
         for (auto p : sem_empty) (void)hipFree(p);
         for (auto p : pinned) (void)hipHostFree(p);
+        for (auto p : stage) (void)hipFree(p);
         if (scratch) (void)hipFree(scratch);
-        if (s_up) (void)hipStreamDestroy(s_up);
-        if (s_down) (void)hipStreamDestroy(s_down);
+        for (hipStream_t st : {s_up, s_down, s_fin})
+            if (st) (void)hipStreamDestroy(st);
         *this = HostPath();
     }
 };
@@ -147,16 +185,16 @@ struct flex_comm {
     size_t max_bytes = 0;
     flex_config_t cfg;
     flex::LaunchShape reduce_shape, copy_shape;            // device path
-    flex::LaunchShape host_reduce_shape, host_copy_shape;  // host paths (kernel engine): few workgroups
+    flex::LaunchShape link_reduce_shape, link_copy_shape;  // kernels that touch pinned memory: few workgroups
+    flex::LaunchShape stage_reduce_shape, stage_copy_shape;  // hybrid engine: kernels that drain a staging buffer
 
     int naux = 0;  // auxiliary (host-staged) paths: path index 1 + a
     HostPath aux[kMaxAux];
     int npaths() const { return 1 + naux; }
 
-    std::vector<TimingRecord> ring;
-    size_t ring_head = 0, ring_count = 0;
-    uint64_t blocking_reads = 0;
-    hipEvent_t t0 = nullptr, t1 = nullptr;  // device-only timing in flex_comm_tune
+    Ring ring;
+    HipEventApi events;
+    hipEvent_t t0 = nullptr, t1 = nullptr;  // whole-call timing in flex_comm_tune
 
     CollState coll[4];  // indexed by flex_coll
 
@@ -168,44 +206,45 @@ struct flex_comm {
     // it, so the producer of one step overlaps the consumer of the previous one:
     // PCIe carries both directions at once.  The slot of a step is its sequence
     // number modulo the ring size, counted since the communicator was created.
+    // In a slot the peers' pieces lie back to back (stride = the step's size
+    // rounded up to 256 bytes), so the hybrid engine brings a whole step back
+    // with one DMA copy.
     int host_path(HostPath& hp, const HostJob& job, size_t bytes) {
         const size_t nslots = hp.pinned.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
-        // even steps: no short remainder step, and a short part is still cut into
-        // a few steps so that the two stages overlap
-        size_t nsteps = (bytes + cfg.chunk_bytes - 1) / cfg.chunk_bytes;
-        size_t want = std::min<size_t>(cfg.pipeline_depth, bytes / std::max<size_t>(cfg.min_step_bytes, 1));
-        nsteps = std::max<size_t>(std::max(nsteps, want), 1);
-        const size_t step = ((bytes + nsteps - 1) / nsteps + 255) / 256 * 256;
-        const bool kernels = hp.engine == FLEX_ENGINE_KERNEL;
+        const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
+        const int engine = hp.engine;
         const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
 
-        for (size_t off = 0; off < bytes; off += step) {
-            const size_t n = std::min(step, bytes - off);
+        size_t off = 0;
+        for (const uint64_t n : steps) {
             const size_t slot = hp.chunk_seq % nslots;
+            const bool reused = hp.chunk_seq >= nslots;
+            const size_t stride = (n + 255) / 256 * 256;
             char* base = (char*)hp.pinned[slot];
             const void* up_src[FLEX_MAX_RANKS];
             void* up_dst[FLEX_MAX_RANKS];
             uint64_t nn[FLEX_MAX_RANKS];
             for (int j = 0; j < job.npeers; ++j) {
                 up_src[j] = job.peer_src[j] + off;
-                up_dst[j] = base + (size_t)j * cfg.chunk_bytes;
+                up_dst[j] = base + (size_t)j * stride;
                 nn[j] = n;
             }
             const uint64_t use = counters ? hp.slot_uses[slot] : 0;  // this is use number `use` of the slot
+
             // producer stage: the slot must have been drained by its previous use
             if (counters) {
                 if (use > 0)
                     HIP_TRY(hipStreamWaitValue64(hp.s_up, hp.sem_empty[slot], use, hipStreamWaitValueGte,
                                                  ~0ull));
-            } else if (hp.chunk_seq >= nslots) {
+            } else if (reused) {
                 HIP_TRY(hipStreamWaitEvent(hp.s_up, hp.ev_empty[slot], 0));
             }
-            if (kernels) {
-                LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, host_copy_shape, hp.s_up));
-            } else {
+            if (engine == FLEX_ENGINE_SDMA) {
                 for (int j = 0; j < job.npeers; ++j)
                     HIP_TRY(hipMemcpyAsync(up_dst[j], up_src[j], n, hipMemcpyDeviceToHost, hp.s_up));
+            } else {
+                LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, link_copy_shape, hp.s_up));
             }
             // hand the filled slot over to the consumer stage
             if (counters) {
@@ -216,26 +255,56 @@ struct flex_comm {
                 HIP_TRY(hipEventRecord(hp.ev_full[slot], hp.s_up));
                 HIP_TRY(hipStreamWaitEvent(hp.s_down, hp.ev_full[slot], 0));
             }
-            if (kernels && job.reduce) {
+
+            // consumer stage
+            if (engine == FLEX_ENGINE_HYBRID) {
+                // one DMA copy brings the step into the slot's staging buffer ...
+                char* stage = hp.stage[slot];
+                if (reused) HIP_TRY(hipStreamWaitEvent(hp.s_down, hp.ev_stage_free[slot], 0));
+                HIP_TRY(hipMemcpyAsync(stage, base, (size_t)(job.npeers - 1) * stride + n, hipMemcpyHostToDevice,
+                                       hp.s_down));
+                HIP_TRY(hipEventRecord(hp.ev_staged[slot], hp.s_down));
+                // ... and a kernel on the third stream finishes the step from there
+                HIP_TRY(hipStreamWaitEvent(hp.s_fin, hp.ev_staged[slot], 0));
+                if (job.reduce) {
+                    const void* in[FLEX_MAX_RANKS];
+                    int j = 0;
+                    for (int r = 0; r < job.nranks; ++r)
+                        in[r] = (r == job.local_index) ? (const void*)(job.local_src + off)
+                                                       : (const void*)(stage + (size_t)(j++) * stride);
+                    LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part + off, n / es, job.dtype,
+                                                     stage_reduce_shape, hp.s_fin));
+                } else {
+                    const void* dn_src[FLEX_MAX_RANKS];
+                    void* dn_dst[FLEX_MAX_RANKS];
+                    for (int j = 0; j < job.npeers; ++j) {
+                        dn_src[j] = stage + (size_t)j * stride;
+                        dn_dst[j] = job.peer_dst[j] + off;
+                    }
+                    LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, stage_copy_shape, hp.s_fin));
+                }
+                HIP_TRY(hipEventRecord(hp.ev_stage_free[slot], hp.s_fin));
+            } else if (engine == FLEX_ENGINE_KERNEL && job.reduce) {
                 // the reduce kernel reads the peers straight from the pinned slot
                 const void* in[FLEX_MAX_RANKS];
                 int j = 0;
                 for (int r = 0; r < job.nranks; ++r)
                     in[r] = (r == job.local_index) ? (const void*)(job.local_src + off) : up_dst[j++];
                 LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part + off, n / es, job.dtype,
-                                                 host_reduce_shape, hp.s_down));
-            } else if (kernels) {
+                                                 link_reduce_shape, hp.s_down));
+            } else if (engine == FLEX_ENGINE_KERNEL) {
                 const void* dn_src[FLEX_MAX_RANKS];
                 void* dn_dst[FLEX_MAX_RANKS];
                 for (int j = 0; j < job.npeers; ++j) {
                     dn_src[j] = up_dst[j];
                     dn_dst[j] = job.peer_dst[j] + off;
                 }
-                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, host_copy_shape, hp.s_down));
+                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, link_copy_shape, hp.s_down));
             } else {
                 for (int j = 0; j < job.npeers; ++j)
                     HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, hp.s_down));
             }
+            // the pinned slot is free again once s_down's part of the step is done
             if (counters) {
                 HIP_TRY(hipStreamWriteValue64(hp.s_down, hp.sem_empty[slot], use + 1, 0));
                 hp.slot_uses[slot] = use + 1;
@@ -243,8 +312,9 @@ struct flex_comm {
                 HIP_TRY(hipEventRecord(hp.ev_empty[slot], hp.s_down));
             }
             ++hp.chunk_seq;
+            off += n;
         }
-        if (!kernels && job.reduce) {
+        if (engine == FLEX_ENGINE_SDMA && job.reduce) {
             // DMA engine: the peers' parts now sit in device scratch (peer_dst)
             const void* in[FLEX_MAX_RANKS];
             int j = 0;
@@ -287,14 +357,9 @@ struct flex_comm {
         return &(m[size_class] = fresh);
     }
 
-    int consume(TimingRecord& rec) {
-        double T[FLEX_MAX_PATHS] = {0, 0, 0, 0};
-        for (int p = 0; p < npaths(); ++p) {
-            if (!(rec.used_mask & (1u << p))) continue;
-            float ms = 0.f;
-            HIP_TRY(hipEventElapsedTime(&ms, rec.fork, rec.done[p]));
-            T[p] = ms * 1e-3;
-        }
+    // One finished split call: book its per-path times and, in adaptive mode,
+    // hand them to the size class's balancer (Stage 2).
+    void consume(const TimingRecord& rec, const double* T) {
         CollState& cs = coll[rec.coll];
         ++cs.samples;
         for (int p = 0; p < FLEX_MAX_PATHS; ++p) {
@@ -310,80 +375,27 @@ struct flex_comm {
                 if (sc->bal.update(T) && memcmp(before, sc->bal.shares, sizeof before) != 0) ++sc->generation;
             }
         }
-        return FLEX_OK;
     }
 
-    // All of a record's events have completed (block: wait until they have).
-    int record_ready(TimingRecord& rec, bool block, bool* ready) {
-        *ready = true;
-        for (int p = FLEX_MAX_PATHS - 1; p >= 0; --p) {
-            if (!(rec.used_mask & (1u << p))) continue;
-            if (block) {
-                HIP_TRY(hipEventSynchronize(rec.done[p]));
-            } else {
-                hipError_t q = hipEventQuery(rec.done[p]);
-                if (q == hipErrorNotReady) {
-                    *ready = false;
-                    return FLEX_OK;
-                }
-                if (q != hipSuccess)
-                    return flex::fail(FLEX_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(q));
-            }
-        }
-        return FLEX_OK;
-    }
-
-    int pop_oldest(bool block, bool* popped) {
-        TimingRecord& rec = ring[ring_head];
-        bool ready = false;
-        int st = record_ready(rec, block, &ready);
-        *popped = false;
-        if (st || !ready) return st;
-        st = consume(rec);
-        ring_head = (ring_head + 1) % kRingSize;
-        --ring_count;
-        *popped = true;
-        return st;
+    int poll(bool block) {
+        return ring.poll(events, [this](const TimingRecord& rec, const double* T) { consume(rec, T); }, block);
     }
 
     // Evaluator poll in front of a collective call: event queries are not
     // allowed while the caller's stream is being captured, so records wait.
     int poll_before_call(hipStream_t stream) {
-        if (ring_count == 0) return FLEX_OK;
+        if (ring.in_flight() == 0) return FLEX_OK;
         hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
         HIP_TRY(hipStreamIsCapturing(stream, &capture));
         return capture == hipStreamCaptureStatusNone ? poll(false) : FLEX_OK;
     }
 
-    int poll(bool block) {
-        while (ring_count > 0) {
-            bool popped = false;
-            int st = pop_oldest(block, &popped);
-            if (st) return st;
-            if (!popped) break;
-        }
-        return FLEX_OK;
-    }
-
-    int acquire_record(TimingRecord** out) {
-        if (ring_count == kRingSize) {
-            // every record is in flight: wait for the oldest one
-            ++blocking_reads;
-            bool popped = false;
-            int st = pop_oldest(true, &popped);
-            if (st) return st;
-        }
-        *out = &ring[(ring_head + ring_count) % kRingSize];
-        ++ring_count;
-        return FLEX_OK;
-    }
-
     // Share, in units, that each auxiliary path of a call of `bytes` per rank
-    // uses now (units[0] is not used).
-    void units_for_call(int c, size_t bytes, uint32_t* units, bool* adaptive, SizeClass** sc_out) {
+    // uses now (units[0] is not used), and the generation of those shares.
+    void units_for_call(int c, size_t bytes, uint32_t* units, bool* adaptive, uint64_t* generation) {
         CollState& cs = coll[c];
         *adaptive = false;
-        *sc_out = nullptr;
+        *generation = 0;
         for (int p = 0; p < FLEX_MAX_PATHS; ++p) units[p] = 0;
         if (nranks < 2) return;
         if (cs.mode == FLEX_SPLIT_STATIC) {
@@ -393,7 +405,7 @@ struct flex_comm {
         SizeClass* sc = class_for_call(c, size_class_of(bytes));
         if (!sc || sc->bal.npaths < 2) return;
         *adaptive = true;
-        *sc_out = sc;
+        *generation = sc->generation;
         for (int p = 1; p < npaths() && p < sc->bal.npaths; ++p)
             units[p] = std::min(sc->bal.shares[p], cfg.max_host_units);
     }
@@ -408,9 +420,9 @@ struct flex_comm {
     }
 
     // Segment starts of a call: path p carries elements [start[p], start[p+1]).
-    bool split_message(int c, size_t count, size_t es, uint64_t* start, bool* adaptive, SizeClass** sc) {
+    bool split_message(int c, size_t count, size_t es, uint64_t* start, bool* adaptive, uint64_t* generation) {
         uint32_t units[FLEX_MAX_PATHS];
-        units_for_call(c, count * es, units, adaptive, sc);
+        units_for_call(c, count * es, units, adaptive, generation);
         flex::partition_paths(count, units, npaths(), cfg.balancer.share_total, cfg.split_align_elems,
                               cfg.min_split_bytes / es, start);
         for (int p = npaths(); p < FLEX_MAX_PATHS; ++p) start[p + 1] = count;
@@ -422,7 +434,7 @@ struct flex_comm {
 
     // A split call records timing events that the Evaluator reads back with
     // the host clock running; inside a stream capture they would never fire.
-    int begin_split_call(int c, size_t bytes, bool adaptive, SizeClass* sc, hipStream_t stream,
+    int begin_split_call(int c, size_t bytes, bool adaptive, uint64_t generation, hipStream_t stream,
                          TimingRecord** rec_out) {
         hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
         HIP_TRY(hipStreamIsCapturing(stream, &capture));
@@ -430,28 +442,42 @@ struct flex_comm {
             return flex::fail(FLEX_ERR_STATE,
                               "a call that uses a host path cannot be captured into a graph: set the host "
                               "share to 0 for captured calls");
-        ++coll[c].split_calls;
         TimingRecord* rec;
-        int st = acquire_record(&rec);
+        int st = ring.acquire(events, [this](const TimingRecord& r, const double* T) { consume(r, T); }, &rec);
         if (st) return st;
+        ++coll[c].split_calls;
         rec->coll = c;
         rec->size_class = size_class_of(bytes);
         rec->adaptive = adaptive;
-        rec->generation = sc ? sc->generation : 0;
-        rec->used_mask = 0;
+        rec->generation = generation;
         *rec_out = rec;
         return FLEX_OK;
+    }
+
+    // A split call failed after begin_split_call: its record's events say
+    // nothing, so the record goes back; whatever the call did enqueue on the
+    // side streams is waited for, so that nothing of it still runs on the
+    // caller's buffers when the error is returned.
+    int abandon_split_call(int c, int status) {
+        ring.abandon();
+        --coll[c].split_calls;
+        for (int a = 0; a < naux; ++a) aux[a].quiesce();
+        return status;
     }
 
     // AllReduce, or (c == FLEX_REDUCESCATTER) the same reduction over the
     // local rank's slice of every input
     int reduce(int c, const char* who, const void* const* bufs, void* out, size_t count, int dtype,
                hipStream_t stream);
+    int split_reduce(TimingRecord* rec, const uint64_t* start, const void* const* bufs, void* out, int dtype,
+                     hipStream_t stream);
     int reducescatter(const void* const* bufs, void* out, size_t recv_count, int dtype, hipStream_t stream);
     // AllGather, or (c == FLEX_ALLTOALL) the same gather over the pieces the
     // peers address to the local rank
     int gather(int c, const char* who, const void* const* slices, void* out, size_t count, int dtype,
                hipStream_t stream);
+    int split_gather(TimingRecord* rec, const uint64_t* start, const void* const* src, void* const* dst,
+                     const uint64_t* bytes, const void* const* slices, size_t es, hipStream_t stream);
     int alltoall(const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream);
     int collective(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream) {
         if (c == FLEX_REDUCESCATTER) return reducescatter(bufs, out, count, dtype, stream);
@@ -462,8 +488,8 @@ struct flex_comm {
     int validate(const char* who, const void* const* bufs, const void* out, size_t count, int dtype);
     int measure_split(int c, const void* const* bufs, void* out, size_t count, int dtype,
                       hipStream_t stream, const uint32_t* units, double* T);
-    int time_device_alone(int c, const void* const* bufs, void* out, size_t count, int dtype,
-                          hipStream_t stream, double* seconds);
+    int time_calls(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream,
+                   const uint32_t* units, uint32_t reps, bool warm, std::vector<double>* seconds);
 };
 
 int flex_comm::validate(const char* who, const void* const* bufs, const void* out, size_t count,
@@ -519,8 +545,8 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     const size_t es = flex::dtype_size(dtype);
     uint64_t start[FLEX_MAX_PATHS + 1];
     bool adaptive;
-    SizeClass* sc;
-    if (!split_message(c, count, es, start, &adaptive, &sc)) {
+    uint64_t generation;
+    if (!split_message(c, count, es, start, &adaptive, &generation)) {
         LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, count, dtype, reduce_shape, stream));
         return FLEX_OK;
     }
@@ -533,9 +559,15 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     }
 
     TimingRecord* rec;
-    st = begin_split_call(c, count * es, adaptive, sc, stream, &rec);
+    st = begin_split_call(c, count * es, adaptive, generation, stream, &rec);
     if (st) return st;
+    st = split_reduce(rec, start, bufs, out, dtype, stream);
+    return st ? abandon_split_call(c, st) : FLEX_OK;
+}
 
+int flex_comm::split_reduce(TimingRecord* rec, const uint64_t* start, const void* const* bufs, void* out,
+                            int dtype, hipStream_t stream) {
+    const size_t es = flex::dtype_size(dtype);
     // fork
     HIP_TRY(hipEventRecord(rec->fork, stream));
 
@@ -566,9 +598,9 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
             job.peer_dst[job.npeers] = hp.scratch ? hp.scratch + (size_t)job.npeers * hp.scratch_stride : nullptr;
             ++job.npeers;
         }
-        st = host_path(hp, job, (hi - lo) * es);
+        int st = host_path(hp, job, (hi - lo) * es);
         if (st) return st;
-        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.s_down));
+        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
         rec->used_mask |= 1u << (a + 1);
         HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));  // join
     }
@@ -607,8 +639,8 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
     const size_t slice_bytes = count * es;
     uint64_t start[FLEX_MAX_PATHS + 1];
     bool adaptive;
-    SizeClass* sc;
-    const bool split = split_message(c, count, es, start, &adaptive, &sc);
+    uint64_t generation;
+    const bool split = split_message(c, count, es, start, &adaptive, &generation);
 
     const void* src[FLEX_MAX_RANKS];
     void* dst[FLEX_MAX_RANKS];
@@ -624,8 +656,14 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
     }
 
     TimingRecord* rec;
-    st = begin_split_call(c, slice_bytes, adaptive, sc, stream, &rec);
+    st = begin_split_call(c, slice_bytes, adaptive, generation, stream, &rec);
     if (st) return st;
+    st = split_gather(rec, start, src, dst, bytes, slices, es, stream);
+    return st ? abandon_split_call(c, st) : FLEX_OK;
+}
+
+int flex_comm::split_gather(TimingRecord* rec, const uint64_t* start, const void* const* src, void* const* dst,
+                            const uint64_t* bytes, const void* const* slices, size_t es, hipStream_t stream) {
     HIP_TRY(hipEventRecord(rec->fork, stream));
 
     LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
@@ -644,9 +682,9 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
             job.peer_dst[job.npeers] = (char*)dst[r] + lo * es;
             ++job.npeers;
         }
-        st = host_path(hp, job, (hi - lo) * es);
+        int st = host_path(hp, job, (hi - lo) * es);
         if (st) return st;
-        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.s_down));
+        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
         rec->used_mask |= 1u << (a + 1);
         HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));
     }
@@ -677,24 +715,25 @@ int flex_comm::measure_split(int c, const void* const* bufs, void* out, size_t c
     return FLEX_OK;
 }
 
-// Median time of the whole message on the device path alone.
-int flex_comm::time_device_alone(int c, const void* const* bufs, void* out, size_t count, int dtype,
-                                 hipStream_t stream, double* seconds) {
+// Whole-call times at fixed shares: events on the caller's stream around each of
+// `reps` calls (after one untimed call if `warm`), appended to *seconds.
+int flex_comm::time_calls(int c, const void* const* bufs, void* out, size_t count, int dtype, hipStream_t stream,
+                          const uint32_t* units, uint32_t reps, bool warm, std::vector<double>* seconds) {
     CollState& cs = coll[c];
     cs.mode = FLEX_SPLIT_STATIC;
-    for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = 0;
-    std::vector<double> td;
-    for (uint32_t k = 0; k < cfg.tune_reps + 1; ++k) {
+    for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = (units && p < npaths()) ? units[p] : 0;
+    for (uint32_t k = 0; k < reps + (warm ? 1u : 0u); ++k) {
         HIP_TRY(hipEventRecord(t0, stream));
         int st = collective(c, bufs, out, count, dtype, stream);
         if (st) return st;
         HIP_TRY(hipEventRecord(t1, stream));
         HIP_TRY(hipEventSynchronize(t1));
+        st = poll(true);
+        if (st) return st;
         float ms = 0.f;
         HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
-        if (k > 0) td.push_back(ms * 1e-3);
+        if (!warm || k > 0) seconds->push_back(ms * 1e-3);
     }
-    *seconds = median_of(td);
     return FLEX_OK;
 }
 
@@ -703,6 +742,7 @@ extern "C" {
 int flex_config_default(flex_config_t* cfg) {
     if (!cfg) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_config_default: cfg is NULL");
     memset(cfg, 0, sizeof *cfg);
+    cfg->struct_size = (uint32_t)sizeof *cfg;
     cfg->chunk_bytes = 4u << 20;
     cfg->num_slots = 2;
     cfg->max_host_units = 2500;
@@ -710,35 +750,30 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->min_split_bytes = 64u << 10;
     cfg->tune_reps = 5;
     cfg->probe_units = 200;
-    // Launch shapes found best on MI355X for the 8 x 256 MiB AllReduce followed by
-    // the 8 x 32 MiB AllGather on buffers that are cold in the Infinity Cache:
+    cfg->tune_accept_check = 1;
+    cfg->accept_pairs = 3;
+    // Launch shape found best on MI355X for the 8 x 256 MiB AllReduce followed by
+    // the 8 x 32 MiB AllGather on buffers that are cold in the memory-side cache:
     // one wavefront per workgroup, one 16-byte vector per lane and input, one
     // workgroup per tile, one load in flight per wavefront in the reduce, loads
-    // and stores both marked non-temporal.  (When the
-    // same 256 MiB output is rewritten call after call it stays resident in the
-    // 256 MB Infinity Cache and plain stores are a few percent faster.)
-    cfg->reduce_threads = 64;
-    cfg->reduce_unroll = 1;
-    cfg->reduce_waves_per_cu = 0;
-    cfg->copy_threads = 64;
-    cfg->copy_unroll = 1;
-    cfg->copy_waves_per_cu = 0;
+    // and stores both marked non-temporal.  (When the same 256 MiB output is
+    // rewritten call after call it stays resident in the 256 MB memory-side
+    // cache and plain stores are a few percent faster.)
+    cfg->launch_shape = FLEX_SHAPE_WAVE;
+    cfg->reduce_serial_loads = 1;
     cfg->reduce_nontemporal = 3;
     cfg->copy_nontemporal = 3;
-    cfg->host_engine = FLEX_ENGINE_KERNEL;
-    cfg->host_blocks = 16;
-    cfg->pipeline_depth = 4;
+    cfg->host_engine = FLEX_ENGINE_HYBRID;
+    cfg->host_blocks = 8;
+    cfg->host_die_shift = 2;
     cfg->min_step_bytes = 256u << 10;
-    cfg->tune_accept_check = 1;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
     cfg->num_aux_paths = 1;
-    cfg->host_die_shift = 2;
-    cfg->reduce_serial_loads = 1;
     flex::balancer_cfg_default(&cfg->balancer);
     return FLEX_OK;
 }
 
-static bool threads_ok(uint32_t t) { return t >= 64 && t <= 1024 && t % 64 == 0; }
+static bool hints_ok(uint32_t nt) { return nt == 0 || nt == 1 || nt == 3; }
 
 int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_per_rank,
                      const flex_config_t* cfg) {
@@ -750,21 +785,20 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     flex_config_t c;
     flex_config_default(&c);
     if (cfg) {
-        flex_config_t d = c;
+        if (cfg->struct_size != sizeof(flex_config_t))
+            return flex::fail(FLEX_ERR_INVALID_ARG,
+                              "flex_comm_create: cfg->struct_size is %u, this library's flex_config_t has %zu bytes "
+                              "(start from flex_config_default)", cfg->struct_size, sizeof(flex_config_t));
         c = *cfg;
-        // zero means "library default" for the launch shapes
-        if (!c.reduce_threads) c.reduce_threads = d.reduce_threads;
-        if (!c.reduce_unroll) c.reduce_unroll = d.reduce_unroll;
-        if (!c.copy_threads) c.copy_threads = d.copy_threads;
-        if (!c.copy_unroll) c.copy_unroll = d.copy_unroll;
     }
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.pipeline_depth < 1 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
-        c.host_die_shift > 3 || c.reduce_serial_loads > 2 || b.share_total == 0 ||
-        c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.probe_units == 0 || !threads_ok(c.reduce_threads) ||
-        !threads_ok(c.copy_threads) || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
+        c.host_blocks > 65536 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
+        c.host_die_shift > 3 || c.reduce_serial_loads > 2 || c.launch_shape > FLEX_SHAPE_BLOCK ||
+        !hints_ok(c.reduce_nontemporal) || !hints_ok(c.copy_nontemporal) || b.share_total == 0 ||
+        c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.accept_pairs < 1 ||
+        c.probe_units == 0 || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_create: configuration out of range");
 
     flex_comm* m = new (std::nothrow) flex_comm;
@@ -788,16 +822,21 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     CREATE_TRY(hipGetDevice(&m->device));
     int cus = 0;
     CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device));
-    m->reduce_shape = {c.reduce_threads, c.reduce_unroll, c.reduce_waves_per_cu, c.reduce_nontemporal,
-                       (uint32_t)cus, 0};
+    const uint32_t threads = c.launch_shape == FLEX_SHAPE_BLOCK ? 256u : 64u;
+    m->reduce_shape = {threads, 1, c.reduce_nontemporal, (uint32_t)cus, 0};
     // 16 tiles per compute unit: half of the wavefront slots of the chip
     m->reduce_shape.serial_min_tiles = c.reduce_serial_loads == 2 ? 1u
                                        : c.reduce_serial_loads == 1 ? 16u * (uint32_t)cus : 0u;
-    m->copy_shape = {c.copy_threads, c.copy_unroll, c.copy_waves_per_cu, c.copy_nontemporal, (uint32_t)cus, 0};
-    // host path kernels: a fixed, small number of workgroups striding over the
-    // step, so that PCIe-bound waves do not crowd the device path off the CUs
-    m->host_reduce_shape = {256, 1, 0, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
-    m->host_copy_shape = {256, 2, 0, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    m->copy_shape = {threads, 1, c.copy_nontemporal, (uint32_t)cus, 0};
+    // kernels that read or write pinned memory over PCIe: a fixed, small number
+    // of workgroups striding over the step, kept on few dies, so that waves
+    // waiting on the link do not crowd the device path off the memory system
+    m->link_reduce_shape = {256, 1, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    m->link_copy_shape = {256, 2, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    // hybrid engine: kernels that drain a staging buffer run at HBM speed and
+    // are over in microseconds; all loads of a tile in flight
+    m->stage_reduce_shape = {256, 1, 0, (uint32_t)cus, 0};
+    m->stage_copy_shape = {256, 2, 0, (uint32_t)cus, 0};
     CREATE_TRY(hipEventCreate(&m->t0));
     CREATE_TRY(hipEventCreate(&m->t1));
 
@@ -818,26 +857,36 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
         per_peer += (size_t)c.split_align_elems * 4 * 2;
         per_peer = std::min(per_peer, max_bytes_per_rank);
         per_peer = (per_peer + 255) / 256 * 256;
+        const size_t slot_bytes = c.chunk_bytes * (size_t)(nranks - 1);
 
         m->naux = (int)c.num_aux_paths;
         for (int a = 0; a < m->naux; ++a) {
             HostPath& hp = m->aux[a];
-            // the first auxiliary path uses the configured engine, the second the other one
-            hp.engine = a == 0 ? (int)c.host_engine : (c.host_engine == FLEX_ENGINE_KERNEL ? FLEX_ENGINE_SDMA
-                                                                                           : FLEX_ENGINE_KERNEL);
+            // the first auxiliary path uses the configured engine, the second the next one
+            hp.engine = (int)((c.host_engine + (uint32_t)a) % 3u);
             // side streams at the default priority
             CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
             CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
+            if (hp.engine == FLEX_ENGINE_HYBRID) CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
             for (uint32_t s = 0; s < c.num_slots; ++s) {
                 void* p = nullptr;
-                CREATE_TRY(hipHostMalloc(&p, c.chunk_bytes * (size_t)(nranks - 1), hipHostMallocDefault));
+                CREATE_TRY(hipHostMalloc(&p, slot_bytes, hipHostMallocDefault));
                 hp.pinned.push_back(p);
-                hipEvent_t e = nullptr;
-                CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-                hp.ev_full.push_back(e);
-                e = nullptr;
-                CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-                hp.ev_empty.push_back(e);
+                for (auto* vec : {&hp.ev_full, &hp.ev_empty}) {
+                    hipEvent_t e = nullptr;
+                    CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                    vec->push_back(e);
+                }
+                if (hp.engine == FLEX_ENGINE_HYBRID) {
+                    char* d = nullptr;
+                    CREATE_TRY(hipMalloc((void**)&d, slot_bytes));
+                    hp.stage.push_back(d);
+                    for (auto* vec : {&hp.ev_staged, &hp.ev_stage_free}) {
+                        hipEvent_t e = nullptr;
+                        CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                        vec->push_back(e);
+                    }
+                }
                 if (c.slot_sync == FLEX_SYNC_COUNTERS) {
                     // stream memory operations need signal memory, 8 bytes per allocation
                     for (auto* vec : {&hp.sem_full, &hp.sem_empty}) {
@@ -856,7 +905,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
         if (c.slot_sync == FLEX_SYNC_COUNTERS) CREATE_TRY(hipDeviceSynchronize());
 
         m->ring.resize(kRingSize);
-        for (auto& rec : m->ring) {
+        for (auto& rec : m->ring.records()) {
             CREATE_TRY(hipEventCreate(&rec.fork));
             for (int p = 0; p < 1 + m->naux; ++p) CREATE_TRY(hipEventCreate(&rec.done[p]));
         }
@@ -869,7 +918,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
 int flex_comm_destroy(flex_comm_t* m) {
     if (!m) return FLEX_OK;
     for (auto& hp : m->aux) hp.destroy();
-    for (auto& rec : m->ring) {
+    for (auto& rec : m->ring.records()) {
         if (rec.fork) (void)hipEventDestroy(rec.fork);
         for (auto e : rec.done)
             if (e) (void)hipEventDestroy(e);
@@ -940,6 +989,14 @@ int flex_set_split(flex_comm_t* comm, int coll, int mode, uint32_t host_units) {
     return flex_set_split_paths(comm, coll, mode, &host_units, 1);
 }
 
+// Balancer settings of this communicator: the configured ones, with the host
+// paths' ceiling.
+static flex_balancer_cfg_t balancer_cfg_of(const flex_comm* m) {
+    flex_balancer_cfg_t bc = m->cfg.balancer;
+    bc.aux_share_cap = m->cfg.max_host_units;
+    return bc;
+}
+
 int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, void* out, size_t count,
                    int dtype, void* hip_stream, flex_tune_result_t* result) {
     if (!comm) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune: comm is NULL");
@@ -953,7 +1010,7 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     const size_t es = flex::dtype_size(dtype);
     const double msg_bytes = (double)count * es;
     const flex_config_t& cfg = comm->cfg;
-    const flex_balancer_cfg_t& bc = cfg.balancer;
+    const flex_balancer_cfg_t bc = balancer_cfg_of(comm);
     const int np = std::max(comm->npaths(), 2);  // a communicator without peers still reports two paths
     flex_tune_result_t res;
     memset(&res, 0, sizeof res);
@@ -972,9 +1029,10 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     if (st) return st;
 
     // Rate of the device path carrying the whole message alone.
-    double t_dev_alone = 0;
-    st = comm->time_device_alone(coll, rank_bufs, out, count, dtype, stream, &t_dev_alone);
+    std::vector<double> alone;
+    st = comm->time_calls(coll, rank_bufs, out, count, dtype, stream, nullptr, cfg.tune_reps, true, &alone);
     if (st) return st;
+    const double t_dev_alone = median_of(alone);
     res.path_bw[FLEX_PATH_DEVICE] = t_dev_alone > 0 ? msg_bytes / t_dev_alone : 0.0;
 
     // Rate of each host path, measured on a probe share of the message with the
@@ -998,39 +1056,70 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     sc.tuned = true;
     if (!(res.path_bw[FLEX_PATH_DEVICE] > 0) || !sc.bal.init_from_bandwidth(np, res.path_bw, bc))
         return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: could not measure the device path");
+    {
+        // a host path never starts above its ceiling: the excess goes to the device path
+        uint32_t s0[FLEX_MAX_PATHS];
+        bool trimmed = false;
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p) s0[p] = sc.bal.shares[p];
+        for (int p = 1; p < np; ++p)
+            if (s0[p] > cfg.max_host_units) {
+                s0[0] += s0[p] - cfg.max_host_units;
+                s0[p] = cfg.max_host_units;
+                trimmed = true;
+            }
+        if (trimmed && !sc.bal.init_from_shares(np, s0, bc))
+            return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: could not set up the starting shares");
+    }
     for (int p = 0; p < np; ++p) res.initial_shares[p] = sc.bal.shares[p];
 
-    auto clamped = [&](uint32_t* units) {
-        for (int p = 0; p < FLEX_MAX_PATHS; ++p)
-            units[p] = p >= 1 && p < np ? std::min(sc.bal.shares[p], cfg.max_host_units) : 0;
+    auto shares_of = [&](uint32_t* units) {
+        for (int p = 0; p < FLEX_MAX_PATHS; ++p) units[p] = p < np ? sc.bal.shares[p] : 0;
     };
 
     // Algorithm 1 with real measurements.
     while (sc.bal.stage == FLEX_STAGE_TUNING) {
+        flex_tune_round_t round;
+        memset(&round, 0, sizeof round);
         uint32_t units[FLEX_MAX_PATHS];
-        clamped(units);
+        shares_of(units);
+        memcpy(round.shares_before, units, sizeof units);
         st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, T);
         if (st) return st;
         if (!sc.bal.update(T))
             return flex::fail(FLEX_ERR_STATE, "flex_comm_tune: unusable path timings (%g s, %g s, %g s)", T[0],
                               T[1], T[2]);
+        for (int p = 0; p < np; ++p)
+            round.path_time_s[p] = (round.shares_before[p] > 0) ? T[p] : 0.0;
+        shares_of(round.shares_after);
+        round.step_after = sc.bal.step;
+        round.active_after = sc.bal.active_mask;
+        ++sc.rounds_run;
+        if (sc.rounds.size() < kMaxTuneRounds) sc.rounds.push_back(round);
     }
     for (int p = 0; p < np; ++p) res.balanced_shares[p] = sc.bal.shares[p];
-    res.device_alone_s = t_dev_alone;
 
-    // Acceptance check: the balanced split must beat the device path alone.
+    // Acceptance check: the balanced split must beat the device path alone by
+    // more than the noise.  Both are timed as whole calls on the caller's
+    // stream, in turns, so that drift hits both alike.
     if (cfg.tune_accept_check && (sc.bal.active_mask & ~1u)) {
         uint32_t units[FLEX_MAX_PATHS];
-        clamped(units);
-        double Tc[FLEX_MAX_PATHS] = {0, 0, 0, 0};
-        st = comm->measure_split(coll, rank_bufs, out, count, dtype, stream, units, Tc);
-        if (st) return st;
-        for (int p = 0; p < np; ++p)
-            if (sc.bal.active_mask & (1u << p)) res.combined_s = std::max(res.combined_s, Tc[p]);
-        // device path alone again, right next to it
-        st = comm->time_device_alone(coll, rank_bufs, out, count, dtype, stream, &res.device_alone_s);
-        if (st) return st;
-        if (!(res.combined_s < res.device_alone_s)) {
+        shares_of(units);
+        std::vector<double> split_s, alone_s;
+        for (uint32_t pair = 0; pair < cfg.accept_pairs; ++pair) {
+            st = comm->time_calls(coll, rank_bufs, out, count, dtype, stream, units, cfg.tune_reps, pair == 0,
+                                  &split_s);
+            if (st) return st;
+            st = comm->time_calls(coll, rank_bufs, out, count, dtype, stream, nullptr, cfg.tune_reps, pair == 0,
+                                  &alone_s);
+            if (st) return st;
+        }
+        res.combined_s = median_of(split_s);
+        res.device_alone_s = median_of(alone_s);
+        res.combined_mad_s = mad_of(split_s);
+        res.device_alone_mad_s = mad_of(alone_s);
+        res.accept_samples = (uint32_t)split_s.size();
+        const double gain = res.device_alone_s - res.combined_s;
+        if (!(gain > 3.0 * std::max(res.combined_mad_s, res.device_alone_mad_s))) {
             sc.bal.revert_to_primary();
             res.reverted = 1;
         }
@@ -1039,8 +1128,9 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     // leave `out` holding a result computed after the last share change
     {
         uint32_t units[FLEX_MAX_PATHS];
-        clamped(units);
+        shares_of(units);
         memcpy(cs.static_units, units, sizeof units);
+        cs.static_units[0] = 0;
         cs.mode = FLEX_SPLIT_STATIC;
     }
     st = comm->collective(coll, rank_bufs, out, count, dtype, stream);
@@ -1063,6 +1153,22 @@ int flex_comm_tune(flex_comm_t* comm, int coll, const void* const* rank_bufs, vo
     return FLEX_OK;
 }
 
+int flex_comm_tune_trace(flex_comm_t* comm, int coll, size_t count, int dtype, flex_tune_round_t* rounds,
+                         uint32_t max_rounds, uint32_t* nrounds) {
+    if (!comm || !nrounds || (max_rounds > 0 && !rounds))
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune_trace: NULL argument");
+    if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
+        return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_tune_trace: unknown collective %d", coll);
+    const size_t es = flex::dtype_size(dtype);
+    if (es == 0) return flex::fail(FLEX_ERR_UNSUPPORTED, "flex_comm_tune_trace: unknown dtype %d", dtype);
+    SizeClass* sc = comm->find_class(coll, size_class_of(count * es));
+    if (!sc || !sc->tuned)
+        return flex::fail(FLEX_ERR_STATE, "flex_comm_tune_trace: this size class was never tuned");
+    *nrounds = sc->rounds_run;
+    for (size_t k = 0; k < sc->rounds.size() && k < max_rounds; ++k) rounds[k] = sc->rounds[k];
+    return FLEX_OK;
+}
+
 int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, const uint32_t* shares) {
     if (!comm || !shares) return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: NULL argument");
     if (coll < FLEX_ALLREDUCE || coll > FLEX_ALLTOALL)
@@ -1076,7 +1182,7 @@ int flex_comm_set_shares(flex_comm_t* comm, int coll, size_t count, int dtype, c
                               shares[p], comm->cfg.max_host_units);
     SizeClass sc;
     sc.tuned = true;
-    if (!sc.bal.init_from_shares(np, shares, comm->cfg.balancer))
+    if (!sc.bal.init_from_shares(np, shares, balancer_cfg_of(comm)))
         return flex::fail(FLEX_ERR_INVALID_ARG, "flex_comm_set_shares: shares must sum to share_total");
     sc.bal.finish_tuning();
     auto& slot = comm->coll[coll].classes[size_class_of(count * es)];
@@ -1107,7 +1213,7 @@ int flex_get_stats(flex_comm_t* comm, int coll, size_t count, int dtype, flex_st
     out->calls = cs.calls;
     out->split_calls = cs.split_calls;
     out->samples = cs.samples;
-    out->blocking_reads = comm->blocking_reads;
+    out->blocking_reads = comm->ring.blocking_reads();
     out->last_count = cs.last_count;
     out->last_split = cs.last_start[1];
     out->mode = cs.mode;

@@ -2,6 +2,7 @@
 #ifndef FLEXLINK_INTERNAL_H
 #define FLEXLINK_INTERNAL_H
 
+#include <algorithm>
 #include <cstddef>
 #include <cstdint>
 #include <vector>
@@ -77,19 +78,51 @@ struct Balancer {
    private:
     void end_tuning_if_done(bool stable);
     void slowest_fastest(const double* T, int* slow, int* fast) const;
-    void move_share(int slow, int fast, uint32_t amount);
+    uint32_t move_share(int slow, int fast, uint32_t amount);  // units moved
     bool times_ok(const double* T) const;
 };
+
+// Step sizes of a host part of `bytes` bytes per peer (see flex_pipeline_plan):
+// min_step, 2 min_step, ... up to chunk, chunk ..., and back down, every step a
+// multiple of 256 bytes, the last one also taking the left-over bytes.
+inline std::vector<uint64_t> plan_steps(uint64_t bytes, uint64_t chunk, uint64_t min_step) {
+    std::vector<uint64_t> steps;
+    if (bytes == 0) return steps;
+    min_step = std::max<uint64_t>((min_step + 255) / 256 * 256, 256);
+    if (min_step > chunk) min_step = chunk;
+    const uint64_t whole = bytes / 256 * 256, loose = bytes - whole;
+    // the ramp: sizes below chunk, doubling
+    std::vector<uint64_t> ramp;
+    for (uint64_t s = min_step; s < chunk; s *= 2) ramp.push_back(s);
+    size_t levels = 0;
+    uint64_t in_ramps = 0;
+    while (levels < ramp.size() && in_ramps + 2 * ramp[levels] <= whole) in_ramps += 2 * ramp[levels++];
+    for (size_t k = 0; k < levels; ++k) steps.push_back(ramp[k]);
+    // what the two ramps leave, in even pieces of at most chunk bytes
+    const uint64_t middle = whole - in_ramps;
+    if (middle > 0) {
+        const uint64_t pieces = (middle + chunk - 1) / chunk;
+        const uint64_t each = ((middle + pieces - 1) / pieces + 255) / 256 * 256;
+        for (uint64_t done = 0; done < middle; done += each) steps.push_back(std::min(each, middle - done));
+    }
+    for (size_t k = levels; k-- > 0;) steps.push_back(ramp[k]);
+    if (loose > 0) {
+        if (!steps.empty() && steps.back() + loose <= chunk)
+            steps.back() += loose;
+        else
+            steps.push_back(loose);
+    }
+    return steps;
+}
 
 // ---- device path launchers (defined in reduce_n.hip / gather_copy.hip) ----
 
 struct LaunchShape {
-    uint32_t threads;       // workgroup size
-    uint32_t unroll;        // 16-byte vectors per thread per input per tile
-    uint32_t waves_per_cu;  // 0 = one workgroup per tile
+    uint32_t threads;       // workgroup size: 64 (one tile of 1 KiB per workgroup) or 256
+    uint32_t unroll;        // copy kernel: 16-byte vectors in flight per thread (1 or 2)
     uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device
-    uint32_t max_blocks;    // 0 = no limit; else the grid never exceeds this many workgroups
+    uint32_t max_blocks;    // 0 = one workgroup per tile; else the grid is this many workgroups striding over the tiles
     // The grid is made 2^block_shift times larger and only every 2^block_shift-th
     // workgroup works: 3 keeps the working workgroups on one of the 8 dies.
     uint32_t block_shift = 0;

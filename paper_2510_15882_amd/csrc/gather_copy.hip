@@ -95,12 +95,12 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     }
 }
 
+// Streaming hints: 0 none, 1 non-temporal loads, 3 non-temporal loads and stores.
 template <int UNROLL>
 int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
-    switch (nt & 3u) {
+    switch (nt) {
         case 0: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, false>), grid, dim3(threads), 0, stream, a); break;
         case 1: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, false>), grid, dim3(threads), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, true>), grid, dim3(threads), 0, stream, a); break;
         default: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, true>), grid, dim3(threads), 0, stream, a); break;
     }
     return (int)hipGetLastError();
@@ -123,15 +123,9 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     if (longest == 0) return 0;
 
     const uint32_t threads = shape.threads;
-    const uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : shape.unroll == 8 ? 8 : 4;
+    const uint32_t unroll = shape.unroll == 2 ? 2 : 1;
     const uint64_t tile_bytes = (uint64_t)threads * unroll * 16;
     uint64_t gx = (longest + tile_bytes - 1) / tile_bytes;
-    if (shape.waves_per_cu) {
-        uint64_t resident = (uint64_t)shape.num_cus * shape.waves_per_cu * 64 / threads;
-        uint64_t per_slice = (resident + n - 1) / n;
-        if (per_slice == 0) per_slice = 1;
-        if (gx > per_slice) gx = per_slice;
-    }
     if (shape.max_blocks) {
         uint64_t per_slice = shape.max_blocks / (uint32_t)n;
         if (per_slice == 0) per_slice = 1;
@@ -143,12 +137,8 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     gx <<= a.shift;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;
-    switch (unroll) {
-        case 1: return launch_one<1>(a, grid, threads, shape.nontemporal, s);
-        case 2: return launch_one<2>(a, grid, threads, shape.nontemporal, s);
-        case 8: return launch_one<8>(a, grid, threads, shape.nontemporal, s);
-        default: return launch_one<4>(a, grid, threads, shape.nontemporal, s);
-    }
+    return unroll == 2 ? launch_one<2>(a, grid, threads, shape.nontemporal, s)
+                       : launch_one<1>(a, grid, threads, shape.nontemporal, s);
 }
 
 }  // namespace flex

@@ -3,12 +3,12 @@
 // Limitations and Future Work), fused over all N contributions.
 //
 // Pure HBM streaming for gfx950: every lane issues one 16-byte load per input
-// per unrolled step (a wavefront covers 1 KiB of each input contiguously) and
+// (a wavefront covers 1 KiB of each input contiguously) and
 // the result leaves through one 16-byte store.  No LDS and no MFMA: 7 adds per
-// 18 bytes.  Two load schedules: UNROLL >= 1 puts all N * UNROLL loads of a
-// tile in flight before the first add; UNROLL == 0 ("serial") keeps ONE load in
-// flight per wavefront - input r+1 is requested only after input r has arrived
-// - and leaves the latency hiding to the 32 wavefronts a compute unit holds.
+// 18 bytes.  Two load schedules: one puts all N loads of a tile in flight
+// before the first add; the other ("serial") keeps ONE load in flight per
+// wavefront - input r+1 is requested only after input r has arrived - and
+// leaves the latency hiding to the 32 wavefronts a compute unit holds.
 // On MI355X the serial schedule is the faster one by 3-7 % for messages of
 // 4 MiB and more per rank (a wavefront's loads return in order, so eight
 // outstanding loads to eight streams can hold each other up; measured, not
@@ -19,6 +19,8 @@
 // value, and rounded once to the element type; nothing here may be compiled
 // with fast-math, reassociation or denormal flushing.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "flexlink_internal.h"
 
@@ -175,7 +177,7 @@ __device__ __forceinline__ void reduce_one_element(const ReduceArgs& a, uint64_t
     }
 }
 
-template <int N, int DT, int UNROLL, bool LDNT, bool STNT>
+template <int N, int DT, bool SERIAL, bool LDNT, bool STNT>
 __global__ void reduce_n_kernel(ReduceArgs a) {
     constexpr uint32_t kElemSize = DT == kF32 ? 4 : 2;
     constexpr uint32_t kVecElems = 16 / kElemSize;
@@ -186,10 +188,7 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     if (blockIdx.x & ((1u << a.shift) - 1u)) return;
     const uint32_t bid = blockIdx.x >> a.shift;
     const uint32_t nblk = gridDim.x >> a.shift;
-    constexpr bool kSerial = UNROLL == 0;
-    constexpr int kUnroll = kSerial ? 1 : UNROLL;
-    const uint64_t tile_vecs = (uint64_t)nthreads * kUnroll;
-    const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
+    const uint64_t ntiles = (a.nvec + nthreads - 1) / nthreads;  // one vector per thread and tile
 
     const u32x4_in* in[N];
 #pragma unroll
@@ -198,31 +197,15 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     u32x4* out = (u32x4*)((char*)a.out + a.head * kElemSize);
 
     for (uint64_t tile = bid; tile < ntiles; tile += nblk) {
-        const uint64_t first = tile * tile_vecs;
-        if (kSerial) {
-            const uint64_t idx = first + tid;
-            if (idx < a.nvec) store16<STNT>(out + idx, reduce_serial<N, DT, LDNT>(in, idx));
-        } else if (first + tile_vecs <= a.nvec) {
-            u32x4 v[kUnroll][N];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-                for (int r = 0; r < N; ++r)
-                    v[u][r] = load16<LDNT>(in[r] + first + (uint64_t)u * nthreads + tid);
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                store16<STNT>(out + first + (uint64_t)u * nthreads + tid, reduce_vectors<N, DT>(v[u]));
+        const uint64_t idx = tile * nthreads + tid;
+        if (idx >= a.nvec) continue;  // ragged last tile
+        if (SERIAL) {
+            store16<STNT>(out + idx, reduce_serial<N, DT, LDNT>(in, idx));
         } else {
-            // ragged last tile
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint64_t idx = first + (uint64_t)u * nthreads + tid;
-                if (idx < a.nvec) {
-                    u32x4 v[N];
+            u32x4 v[N];
 #pragma unroll
-                    for (int r = 0; r < N; ++r) v[r] = load16<LDNT>(in[r] + idx);
-                    store16<STNT>(out + idx, reduce_vectors<N, DT>(v));
-                }
-            }
+            for (int r = 0; r < N; ++r) v[r] = load16<LDNT>(in[r] + idx);
+            store16<STNT>(out + idx, reduce_vectors<N, DT>(v));
         }
     }
 
@@ -235,40 +218,35 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     }
 }
 
-template <int N, int DT, int UNROLL>
+// Streaming hints: 0 none, 1 non-temporal loads, 3 non-temporal loads and stores.
+template <int N, int DT, bool SERIAL>
 int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
-    switch (nt & 3u) {
-        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, false, true>), dim3(grid), dim3(threads), 0, stream, a); break;
-        default: hipLaunchKernelGGL((reduce_n_kernel<N, DT, UNROLL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+    switch (nt) {
+        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
+        default: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
     }
     return (int)hipGetLastError();
 }
 
 template <int N, int DT>
-int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
-             hipStream_t stream) {
-    switch (unroll) {
-        case 0: return launch_one<N, DT, 0>(a, grid, threads, nt, stream);
-        case 1: return launch_one<N, DT, 1>(a, grid, threads, nt, stream);
-        case 2: return launch_one<N, DT, 2>(a, grid, threads, nt, stream);
-        default: return launch_one<N, DT, 4>(a, grid, threads, nt, stream);
-    }
+int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, bool serial, uint32_t nt, hipStream_t stream) {
+    return serial ? launch_one<N, DT, true>(a, grid, threads, nt, stream)
+                  : launch_one<N, DT, false>(a, grid, threads, nt, stream);
 }
 
 template <int DT>
-int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t unroll, uint32_t nt,
+int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, bool serial, uint32_t nt,
                  hipStream_t stream) {
     switch (n) {
-        case 1: return launch_n<1, DT>(a, grid, threads, unroll, nt, stream);
-        case 2: return launch_n<2, DT>(a, grid, threads, unroll, nt, stream);
-        case 3: return launch_n<3, DT>(a, grid, threads, unroll, nt, stream);
-        case 4: return launch_n<4, DT>(a, grid, threads, unroll, nt, stream);
-        case 5: return launch_n<5, DT>(a, grid, threads, unroll, nt, stream);
-        case 6: return launch_n<6, DT>(a, grid, threads, unroll, nt, stream);
-        case 7: return launch_n<7, DT>(a, grid, threads, unroll, nt, stream);
-        default: return launch_n<8, DT>(a, grid, threads, unroll, nt, stream);
+        case 1: return launch_n<1, DT>(a, grid, threads, serial, nt, stream);
+        case 2: return launch_n<2, DT>(a, grid, threads, serial, nt, stream);
+        case 3: return launch_n<3, DT>(a, grid, threads, serial, nt, stream);
+        case 4: return launch_n<4, DT>(a, grid, threads, serial, nt, stream);
+        case 5: return launch_n<5, DT>(a, grid, threads, serial, nt, stream);
+        case 6: return launch_n<6, DT>(a, grid, threads, serial, nt, stream);
+        case 7: return launch_n<7, DT>(a, grid, threads, serial, nt, stream);
+        default: return launch_n<8, DT>(a, grid, threads, serial, nt, stream);
     }
 }
 
@@ -300,23 +278,14 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     a.nvec = (count - head) / vec_elems;
 
     const uint32_t threads = shape.threads;
-    uint32_t unroll = shape.unroll == 1 ? 1 : shape.unroll == 2 ? 2 : 4;
     // The serial schedule pays N load latencies per tile: it wins once the
     // message keeps every wavefront slot of the chip busy several times over,
     // and loses on short messages whose time is one wavefront's lifetime.
-    if (shape.serial_min_tiles && (a.nvec + 63) / 64 >= shape.serial_min_tiles) unroll = 0;  // 1 KiB tiles
-    const uint64_t tile_vecs = (uint64_t)threads * (unroll ? unroll : 1);
-    const uint64_t ntiles = (a.nvec + tile_vecs - 1) / tile_vecs;
+    const bool serial = shape.serial_min_tiles && (a.nvec + 63) / 64 >= shape.serial_min_tiles;  // 1 KiB tiles
+    const uint64_t ntiles = (a.nvec + threads - 1) / threads;
     const uint64_t nscalar = count - a.nvec * vec_elems;
     const uint64_t scalar_blocks = (nscalar + threads - 1) / threads;
-    uint64_t grid = ntiles;
-    uint64_t resident = (uint64_t)shape.num_cus * (shape.waves_per_cu ? shape.waves_per_cu : 1) * 64 / threads;
-    if (resident == 0) resident = 1;
-    if (shape.waves_per_cu && grid > resident) grid = resident;
-    // one-by-one elements: enough blocks to spread them, but never more than a
-    // persistent grid's worth beyond the tiles
-    uint64_t sgrid = scalar_blocks < resident * 8 ? scalar_blocks : resident * 8;
-    if (grid < sgrid) grid = sgrid;
+    uint64_t grid = std::max(ntiles, std::min<uint64_t>(scalar_blocks, 8ull * shape.num_cus));
     if (shape.max_blocks && grid > shape.max_blocks) grid = shape.max_blocks;
     if (grid == 0) grid = 1;
     a.shift = shape.block_shift > 8 ? 8 : shape.block_shift;
@@ -325,10 +294,10 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
 
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)
-        return launch_dtype<kBF16>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+        return launch_dtype<kBF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
     if (dtype == FLEX_F16)
-        return launch_dtype<kF16>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
-    return launch_dtype<kF32>(n, a, (uint32_t)grid, threads, unroll, shape.nontemporal, s);
+        return launch_dtype<kF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
+    return launch_dtype<kF32>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
 }
 
 }  // namespace flex

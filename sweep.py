@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
 """Configurations 0, 3 and 4 on one MI355X: message-size sweep with the
 two-stage balancer, the tensor-parallel prefill shape, and the small
-launch-bound message.  Prints one JSON line per case.
+launch-bound message.  Prints one JSON line per case; --summary FILE also
+writes the figures as a plain-text table.
 
-    python -m paper_2510_15882_amd.sweep --config 3      # 1..1024 MiB per rank, AR and AG
-    python -m paper_2510_15882_amd.sweep --config 3 --dtype f32   # same byte sizes in binary32 (or f16)
-    python -m paper_2510_15882_amd.sweep --config 4      # 65536 x 5120 bf16 AllReduce, 50 calls
-    python -m paper_2510_15882_amd.sweep --config 0      # 1 MiB fp32 AllReduce: latency
+    python sweep.py --config 3      # 1..1024 MiB per rank, AR and AG
+    python sweep.py --config 3 --dtype f32   # same byte sizes in binary32 (or f16)
+    python sweep.py --config 4      # 65536 x 5120 bf16 AllReduce, 50 calls
+    python sweep.py --config 0      # 1 MiB fp32 AllReduce: latency
 
 Per case: Stage 1 on the hardware (rates of both paths, bandwidth-proportional
-initial shares, Algorithm 1), then adaptive calls (Stage 2), then the same
-number of device-only calls interleaved block by block for an A/B comparison.
+initial shares, Algorithm 1, acceptance check), then adaptive calls (Stage 2),
+then the same number of device-only calls interleaved block by block for an A/B
+comparison.  For messages of 640 MiB per rank and more the host path is also
+forced live (the shares Algorithm 1 balanced at, before the acceptance check)
+and compared with the device path alone the same way: the only sizes where what
+PCIe can carry during one call exceeds what a split call costs.
 """
 import argparse
 import json
@@ -19,8 +24,8 @@ import time
 
 import torch
 
-from . import binding as fx
-from . import workloads as wl
+from paper_2510_15882_amd import binding as fx
+from paper_2510_15882_amd import workloads as wl
 
 N = 8
 
@@ -80,6 +85,30 @@ class Case:
         fx.flex_comm_destroy(self.comm)
 
 
+def live_ab(c, w, units, blocks=12, per_block=10):
+    """Host path forced live at `units` against the device path alone, in
+    alternating blocks of calls; Stage 2 keeps running in the live blocks."""
+    fx.flex_comm_set_shares(c.comm, c.coll, w.count, w.dtype, [10000 - units, units])
+    live_ms, device_ms = [], []
+    for _ in range(blocks):
+        fx.flex_set_split(c.comm, c.coll, fx.FLEX_SPLIT_ADAPTIVE)
+        live_ms += c.timed(per_block)
+        fx.flex_evaluator_drain(c.comm)
+        fx.flex_set_split(c.comm, c.coll, fx.FLEX_SPLIT_STATIC, 0)
+        device_ms += c.timed(per_block)
+    st = fx.flex_get_stats(c.comm, c.coll, w.count, w.dtype)
+    a, d = median(live_ms), median(device_ms)
+    noise = 3 * max(mad(live_ms), mad(device_ms))
+    # what PCIe could carry while the device path handles the rest, at 45 GB/s each way
+    pcie_share = (d * 1e-3) * 45e9 / ((N - 1) * w.count * c.bufs[0].element_size())
+    return {"host_share_units_start": units, "host_share_units_end": int(st.balancer.shares[1]),
+            "live_ms": a, "device_only_ms": d, "mad_ms": [mad(live_ms), mad(device_ms)], "calls_each": len(live_ms),
+            "gain_ms": d - a, "three_mad_ms": noise, "live_faster": bool(d - a > noise),
+            "live_slower": bool(a - d > noise), "last_path_times_ms": [t * 1e3 for t in list(st.last_time_s)[:2]],
+            "ideal_host_share_pct_at_45GBs": 100.0 * pcie_share,
+            "ideal_gain_ms": d * pcie_share / (1.0 + pcie_share)}
+
+
 def run_case(w, windows=20, cfg=None):
     c = Case(w, cfg=cfg)
     bc = fx.flex_config_default().balancer
@@ -104,6 +133,7 @@ def run_case(w, windows=20, cfg=None):
         "initial_host_share_pct": res.initial_shares[1] / 100.0,
         "balanced_host_share_pct": res.balanced_shares[1] / 100.0, "stage1_iterations": res.iterations,
         "balanced_split_ms": res.combined_s * 1e3, "device_alone_ms": res.device_alone_s * 1e3,
+        "acceptance_mad_ms": [res.combined_mad_s * 1e3, res.device_alone_mad_s * 1e3],
         "reverted_to_device_only": bool(res.reverted), "stage1_host_share_pct": res.shares[1] / 100.0,
         "host_active_after_stage1": bool(res.active_mask & 2),
         "stage2_windows": windows, "stage2_adjustments": int(st.balancer.adjustments),
@@ -116,6 +146,9 @@ def run_case(w, windows=20, cfg=None):
         "combined_faster": bool(d - a > 3 * max(mad(adaptive_ms), mad(device_ms))),
         "calls_each": calls,
     }
+    if w.bytes_per_rank >= 640 * wl.MIB:
+        units = res.balanced_shares[1] or res.initial_shares[1] or 20
+        out["host_path_forced_live"] = live_ab(c, w, units)
     c.close()
     return out
 
@@ -148,6 +181,8 @@ def run_prefill(calls=50):
     st = fx.flex_get_stats(c.comm, c.coll, w.count, w.dtype)
     out["host_share_pct_after"] = st.balancer.shares[1] / 100.0
     out["blocking_reads"] = int(st.blocking_reads)
+    units = res.balanced_shares[1] or res.initial_shares[1] or 20
+    out["host_path_forced_live"] = live_ab(c, w, units)
     c.close()
     return out
 
@@ -207,9 +242,52 @@ def run_small():
     return out
 
 
+def summary_lines(r):
+    """One case as a few lines of plain text."""
+    if r["config"] == 0:
+        return ["cfg0 %s: event-bracketed single call %.2f us; back to back %.2f us per call (%.0f GB/s); graph "
+                "replay %.2f us per call (%.0f GB/s); rotating over 64 cold buffer sets %.2f us per call (%.0f GB/s)"
+                % (r["case"], r["event_bracketed_single_call_us"], r["back_to_back_us_per_call"],
+                   r["back_to_back_hbm_GBs"], r["graph_replay_us_per_call"], r["graph_replay_hbm_GBs"],
+                   r["rotating_64_buffer_sets_us_per_call"], r["rotating_hbm_GBs"])]
+    lines = ["cfg%d %s (%g MiB per rank)" % (r["config"], r["case"], r["MiB_per_rank"]),
+             "  path rates (message GB/s) device %.1f, host %.2f; InitializeShares host %.2f %%; Algorithm 1: %s "
+             "iterations, balanced host share %.2f %%"
+             % (r["path_rate_GBs"][0], r["path_rate_GBs"][1], r["initial_host_share_pct"],
+                r.get("stage1_iterations", "?"), r["balanced_host_share_pct"]),
+             "  acceptance check: balanced split %.4f ms vs device alone %.4f ms -> %s; host share after Stage 1 %.2f %%"
+             % (r["balanced_split_ms"], r["device_alone_ms"],
+                "reverted to device-only" if r["reverted_to_device_only"] else "kept", r["stage1_host_share_pct"])]
+    if "adaptive_ms" in r:
+        lines.append("  %d Stage-2 windows: converged host share %.2f %%, %d adjustments; adaptive %.4f ms (MAD %.4f) vs "
+                     "device-only %.4f ms (MAD %.4f), %d calls each, interleaved -> combined faster: %s"
+                     % (r["stage2_windows"], r["converged_host_share_pct"], r["stage2_adjustments"], r["adaptive_ms"],
+                        r["mad_ms"][0], r["device_only_ms"], r["mad_ms"][1], r["calls_each"], r["combined_faster"]))
+        lines.append("  adaptive: HBM %.0f GB/s, algbw %.1f GB/s; device-only: HBM %.0f GB/s"
+                     % (r["adaptive_hbm_GBs"], r["adaptive_algbw_GBs"], r["device_only_hbm_GBs"]))
+    else:
+        lines.append("  50 calls back to back on one stream: adaptive %.4f ms per call (HBM %.0f GB/s, algbw %.1f GB/s), "
+                     "device-only %.4f ms per call (HBM %.0f GB/s); host share afterwards %.2f %%; blocking reads %d"
+                     % (r["adaptive_ms_per_call"], r["adaptive_hbm_GBs"], r["adaptive_algbw_GBs"],
+                        r["device_only_ms_per_call"], r["device_only_hbm_GBs"], r["host_share_pct_after"],
+                        r["blocking_reads"]))
+    live = r.get("host_path_forced_live")
+    if live:
+        lines.append("  host path forced live at %d units (ends at %d): %.4f ms (MAD %.4f) vs device-only %.4f ms (MAD %.4f), "
+                     "%d calls each in alternating blocks; gain %.4f ms against 3 x MAD %.4f ms -> %s; PCIe at 45 GB/s "
+                     "could carry %.2f %% in that time (ideal gain %.4f ms)"
+                     % (live["host_share_units_start"], live["host_share_units_end"], live["live_ms"], live["mad_ms"][0],
+                        live["device_only_ms"], live["mad_ms"][1], live["calls_each"], live["gain_ms"],
+                        live["three_mad_ms"], "faster" if live["live_faster"] else
+                        ("slower" if live["live_slower"] else "no difference beyond the noise"),
+                        live["ideal_host_share_pct_at_45GBs"], live["ideal_gain_ms"]))
+    return lines
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, required=True, choices=[0, 3, 4])
+    ap.add_argument("--summary", default=None, help="append the cases as plain text to this file")
     ap.add_argument("--windows", type=int, default=20)
     ap.add_argument("--max-mib", type=int, default=1024)
     ap.add_argument("--dtype", default="bf16", choices=sorted(wl.DTYPE_NAMES),
@@ -218,16 +296,22 @@ def main():
     assert torch.cuda.is_available(), "needs the GPU"
     fx.lib()
     torch.cuda.set_device(0)
+    def emit(r):
+        print(json.dumps(r), flush=True)
+        if args.summary:
+            with open(args.summary, "a") as f:
+                f.write("\n".join(summary_lines(r)) + "\n")
+
     if args.config == 0:
-        print(json.dumps(run_small()), flush=True)
+        emit(run_small())
     elif args.config == 4:
-        print(json.dumps(run_prefill()), flush=True)
+        emit(run_prefill())
     else:
         for w in wl.sweep_workloads(args.dtype):
             if w.bytes_per_rank > args.max_mib * wl.MIB:
                 continue
             log("case", w.name)
-            print(json.dumps(run_case(w, windows=args.windows)), flush=True)
+            emit(run_case(w, windows=args.windows))
             torch.cuda.empty_cache()
 
 

@@ -8,7 +8,9 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import balancer as ob
 from oracle import collectives as oc
+from oracle import partition as op
 from paper_2510_15882_amd import binding as fx
 from paper_2510_15882_amd import workloads as wl
 
@@ -75,6 +77,84 @@ def oracle_allgather(slices):
 
 
 COUNTS = [0, 1, 7, 8, 9, 2047, 2048, 2049, 65536, (1 << 20) + 3]
+
+
+# ---- the balancer on hardware, replayed through the oracle ----------------
+#
+# The library's Stage 1 and Stage 2 run on times measured on the GPU.  The same
+# times are fed to oracle/balancer.py, which must then take the same decisions:
+# same shares after every Algorithm-1 iteration and after every adaptive call.
+
+def live_set(mask, npaths):
+    return {p for p in range(npaths) if mask >> p & 1}
+
+
+def ceiling(cfg, npaths):
+    return [None] + [cfg.max_host_units] * (npaths - 1)
+
+
+def check_stage1_against_oracle(comm, coll, count, dtype, res, cfg, npaths=2):
+    bc = cfg.balancer
+    # InitializeShares: bandwidth-proportional, a host path never above its ceiling
+    want0 = ob.initialize_shares(list(res.path_bw)[:npaths], bc.share_total)
+    for p in range(1, npaths):
+        excess = max(want0[p] - cfg.max_host_units, 0)
+        want0[p] -= excess
+        want0[0] += excess
+    assert list(res.initial_shares)[:npaths] == want0
+    rounds, nrounds = fx.flex_comm_tune_trace(comm, coll, count, dtype)
+    assert nrounds == res.iterations == len(rounds)
+    pending = list(rounds)
+
+    def replay(S, live):
+        r = pending.pop(0)
+        assert list(r.shares_before)[:npaths] == S, "the library measured at other shares than the oracle holds"
+        return list(r.path_time_s)[:npaths]
+    trace = []
+    S, live = ob.initial_tune(want0, replay, step0=bc.initial_step, threshold=bc.convergence_threshold,
+                              stability_required=bc.stability_required, max_iters=bc.max_tune_iters, trace=trace,
+                              cap=ceiling(cfg, npaths))
+    assert not pending, "the library ran more Algorithm-1 iterations than the oracle"
+    assert len(trace) == nrounds
+    for t, r in zip(trace, rounds):
+        assert t["S"] == list(r.shares_after)[:npaths] and t["step"] == r.step_after
+        assert set(t["active"]) == live_set(r.active_after, npaths)
+    assert S == list(res.balanced_shares)[:npaths]
+    if not res.reverted:
+        assert S == list(res.shares)[:npaths] and live == live_set(res.active_mask, npaths)
+    return trace
+
+
+class Stage2Twin:
+    """oracle.balancer.RuntimeAdjuster fed with the times the library's Evaluator read back."""
+
+    def __init__(self, comm, coll, count, dtype, cfg, npaths=2):
+        self.args = (comm, coll, count, dtype)
+        self.npaths = npaths
+        st = fx.flex_get_stats(*self.args)
+        assert st.balancer.stage == fx.FLEX_STAGE_RUNTIME and st.balancer.window_fill == 0
+        bc = cfg.balancer
+        self.twin = ob.RuntimeAdjuster(list(st.balancer.shares)[:npaths], live_set(st.balancer.active_mask, npaths),
+                                       window=bc.window, threshold=bc.runtime_threshold, step=bc.runtime_step,
+                                       cap=ceiling(cfg, npaths))
+        self.samples = st.samples
+        self.moves = []
+
+    def after_call(self):
+        """Call after every adaptive collective call: drains the Evaluator and compares."""
+        torch.cuda.synchronize()
+        fx.flex_evaluator_drain(self.args[0])
+        st = fx.flex_get_stats(*self.args)
+        assert st.samples - self.samples in (0, 1)
+        if st.samples > self.samples:                 # the call was split: one sample per call
+            self.samples = st.samples
+            before = list(self.twin.S)
+            if self.twin.observe(list(st.last_time_s)[:self.npaths]):
+                self.moves.append([b - a for a, b in zip(before, self.twin.S)])
+        assert list(st.balancer.shares)[:self.npaths] == self.twin.S, "library and oracle shares differ"
+        assert live_set(st.balancer.active_mask, self.npaths) == self.twin.C_active
+        assert st.balancer.adjustments == self.twin.adjustments
+        return st
 
 
 # ------------------------------------------------------------ device path
@@ -199,17 +279,15 @@ def test_allgather_misaligned_and_in_place():
             assert wl.to_numpy_bits(out2).tobytes() == want.tobytes(), ("in place", units)
 
 
-@pytest.mark.parametrize("threads,unroll,waves,nt", [
-    (64, 1, 0, 0), (128, 2, 0, 1), (256, 4, 0, 2), (512, 2, 8, 3), (1024, 4, 4, 0), (256, 1, 16, 1), (256, 8, 2, 3)])
-def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
+@pytest.mark.parametrize("shape", [fx.FLEX_SHAPE_WAVE, fx.FLEX_SHAPE_BLOCK])
+@pytest.mark.parametrize("nt", [0, 1, 3])
+def test_every_launch_shape_gives_the_same_bits(shape, nt):
     count = (1 << 21) + 12345
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want_ar = oracle_allreduce(bufs)
     want_ag = oracle_allgather(bufs)
     for serial in (0, 1, 2):
-        with Comm(reduce_threads=threads, reduce_unroll=min(unroll, 4), reduce_waves_per_cu=waves,
-                  reduce_serial_loads=serial, copy_threads=threads, copy_unroll=unroll, copy_waves_per_cu=waves,
-                  reduce_nontemporal=nt, copy_nontemporal=nt) as comm:
+        with Comm(launch_shape=shape, reduce_serial_loads=serial, reduce_nontemporal=nt, copy_nontemporal=nt) as comm:
             out = torch.empty(count, dtype=torch.bfloat16, device=DEV)
             fx.flex_allreduce_local(comm, bufs, out)
             out2 = torch.empty(8 * count, dtype=torch.bfloat16, device=DEV)
@@ -217,11 +295,14 @@ def test_every_launch_shape_gives_the_same_bits(threads, unroll, waves, nt):
             torch.cuda.synchronize()
             assert_same_bits(out, want_ar, "allreduce, serial %d" % serial)
             assert wl.to_numpy_bits(out2).tobytes() == want_ag.tobytes()
+    for bad in (dict(reduce_nontemporal=2), dict(copy_nontemporal=4), dict(launch_shape=2)):
+        with pytest.raises(fx.FlexError):
+            Comm(**bad).__enter__()
 
 
 # ---------------------------------------------------------- ReduceScatter
 
-@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("engine", [0, 1, 2])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_reducescatter_is_the_rank_slice_and_composes_to_allreduce(dtype, engine):
     n = 8
@@ -262,7 +343,8 @@ def test_alltoall_receive_buffer(dtype):
     for cnt in (0, 1, 2049, 40001, (1 << 17) + 2048):
         bufs = [wl.random_bits(n * cnt, dtype, 60 + r, DEV) for r in range(n)]
         host = [wl.to_numpy_bits(b) for b in bufs]
-        for rank, units, engine, paths in ((0, 0, 0, 1), (3, 1500, 0, 1), (7, 1500, 1, 1), (5, 700, 0, 2)):
+        for rank, units, engine, paths in ((0, 0, 0, 1), (3, 1500, 0, 1), (7, 1500, 1, 1), (2, 1500, 2, 1), (5, 700, 0, 2),
+                                           (6, 700, 2, 2)):
             with Comm(rank=rank, max_host_units=10000, host_engine=engine, num_aux_paths=paths,
                       min_step_bytes=16 << 10) as comm:
                 fx.flex_set_split_paths(comm, fx.FLEX_ALLTOALL, fx.FLEX_SPLIT_STATIC, (units,) * paths)
@@ -313,7 +395,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
             lead0 = rng.randrange(0, 16 // es)
             leads = [lead0 if same_lead else rng.randrange(0, 16 // es) for _ in range(nranks)]
             out_lead = lead0 if rng.random() < 0.7 else rng.randrange(0, 16 // es)
-            engine, sync = rng.randrange(2), rng.randrange(2)
+            engine, sync = rng.randrange(3), rng.randrange(2)
             chunk = rng.choice([16 << 10, 64 << 10, 1 << 20])
             shift, paths = rng.randrange(4), rng.choice([1, 1, 2])
             units = rng.choice([0, 1, 37, 500, 2500, 6000, 10000])
@@ -363,7 +445,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
 
 # ------------------------------------------------- split over both paths
 
-ENGINES = [fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
+ENGINES = [fx.FLEX_ENGINE_HYBRID, fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -373,10 +455,11 @@ def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype, engine):
     w = wl.config(0) if dtype == torch.float32 else wl.config(2)
     bufs = wl.make_rank_buffers(w, DEV, count=count)
     want = oracle_allreduce(bufs)
-    for chunk, slots, depth in ((64 << 10, 2, 4), (4 << 20, 2, 1), (256 << 10, 3, 4), (4 << 20, 1, 8)):
+    for chunk, slots, min_step in ((64 << 10, 2, 4 << 10), (4 << 20, 2, 4 << 20), (256 << 10, 3, 32 << 10),
+                                   (4 << 20, 1, 32 << 10)):
         for rank in (0, 3, 7):
             with Comm(rank=rank, max_host_units=10000, chunk_bytes=chunk, num_slots=slots, host_engine=engine,
-                      pipeline_depth=depth, min_step_bytes=32 << 10) as comm:
+                      min_step_bytes=min_step) as comm:
                 for units in (0, 1, 500, 1200, 2200, 10000):
                     say("allreduce split", dtype, chunk, rank, units)
                     fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
@@ -385,7 +468,7 @@ def test_allreduce_bits_do_not_depend_on_split_chunk_or_rank(dtype, engine):
                     torch.cuda.synchronize()
                     assert_same_bits(out, want, "chunk %d rank %d units %d" % (chunk, rank, units))
                     st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, dtype)
-                    assert st.last_split == fx.flex_partition(count, units, 10000, 2048, (64 << 10) // out.element_size())
+                    assert st.last_split == op.partition(count, units, 10000, 2048, (64 << 10) // out.element_size())
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -406,8 +489,9 @@ def test_allgather_bits_do_not_depend_on_split_chunk_or_rank(engine):
                     assert wl.to_numpy_bits(out).tobytes() == want, (chunk, rank, units)
 
 
+@pytest.mark.parametrize("engine", [fx.FLEX_ENGINE_HYBRID, fx.FLEX_ENGINE_KERNEL])
 @pytest.mark.parametrize("shift", [0, 1, 2, 3])
-def test_host_kernels_confined_to_fewer_dies_give_the_same_bits(shift):
+def test_host_kernels_confined_to_fewer_dies_give_the_same_bits(shift, engine):
     # the host-path grids are 2^shift times larger and only every 2^shift-th
     # workgroup works; ragged counts, every alignment fallback of the copy
     count = (1 << 20) + 2048 + 5
@@ -416,7 +500,7 @@ def test_host_kernels_confined_to_fewer_dies_give_the_same_bits(shift):
     want_ag = oracle_allgather(bufs).tobytes()
     for blocks in (1, 16, 100):
         with Comm(max_host_units=10000, host_blocks=blocks, host_die_shift=shift, chunk_bytes=256 << 10,
-                  min_step_bytes=32 << 10) as comm:
+                  min_step_bytes=32 << 10, host_engine=engine) as comm:
             for units in (1, 700, 10000):
                 say("die shift", shift, blocks, units)
                 fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
@@ -571,7 +655,7 @@ def test_three_paths_give_the_same_bits(first_engine, sync):
                                  "reducescatter %s" % (shares,))
                 st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
                 assert st.npaths == 3
-                assert list(st.last_start)[:3] == fx.flex_partition_paths(count, [0, *shares], 10000, 2048, 32768)[:3]
+                assert list(st.last_start)[:3] == op.partition_paths(count, [0, *shares], 10000, 2048, 32768)[:3]
             fx.flex_evaluator_drain(comm)
             st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
             assert st.samples == st.split_calls == 7
@@ -583,10 +667,12 @@ def test_three_paths_give_the_same_bits(first_engine, sync):
 
 
 def test_three_path_balancer_on_hardware():
-    # Algorithm 1 with three real paths, then Stage 2 from installed shares
+    # Algorithm 1 with three real paths, then Stage 2 from installed shares; every
+    # decision is checked against the oracle fed with the same measured times
     count = 64 * wl.MIB        # 128 MiB per rank
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
     want = oracle_allreduce(bufs)
+    cfg = fx.flex_config_default()
     with Comm(max_bytes=count * 2, num_aux_paths=2) as comm:
         out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
         res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
@@ -595,30 +681,23 @@ def test_three_path_balancer_on_hardware():
         assert_same_bits(out, want, "after tune")
         assert sum(res.shares) == 10000 and sum(res.initial_shares) == 10000 and res.iterations <= 100
         assert res.path_bw[0] > 0 and res.path_bw[1] > 0 and res.path_bw[2] > 0
-        denom = res.path_bw[0] + res.path_bw[1] + res.path_bw[2]
-        assert res.initial_shares[1] == int(10000 * res.path_bw[1] / denom)
-        assert res.initial_shares[2] == int(10000 * res.path_bw[2] / denom)
+        trace = check_stage1_against_oracle(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, res, cfg, npaths=3)
+        say("stage 1 on three paths:", [(t["slow"], t["S"]) for t in trace])
         if res.reverted:
             assert list(res.shares)[:3] == [10000, 0, 0]
         # Stage 2 on three live paths
         fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9880, 60, 60])
         fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
-        before = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16).samples
-        traj = [[9880, 60, 60]]
+        twin = Stage2Twin(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, cfg, npaths=3)
         for k in range(60):
             fx.flex_allreduce_local(comm, bufs, out)
+            st = twin.after_call()
             if k % 10 == 9:
-                torch.cuda.synchronize()
                 assert_same_bits(out, want, "adaptive call %d" % k)
-                fx.flex_evaluator_drain(comm)
-                st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
-                traj.append(list(st.balancer.shares)[:3])
-        say("stage2 on three paths", traj, st.as_dict())
-        for a, b in zip(traj, traj[1:]):
-            assert sum(b) == 10000
-            moved = [y - x for x, y in zip(a, b)]
-            assert sorted(moved) in ([0, 0, 0], [-4, 0, 4])      # one fixed step from one path to another
-        assert st.samples - before == 60 and st.last_time_s[2] > 0
+        say("stage2 on three paths: moves", twin.moves, st.as_dict())
+        assert st.samples == twin.samples and st.last_time_s[2] > 0 and len(twin.moves) <= 6
+        for m in twin.moves:
+            assert sorted(m) == [-4, 0, 4]          # one fixed step from one path to another
 
 
 # --------------------------------------------------------- full-size configs
@@ -659,36 +738,113 @@ def test_config2_allreduce_bf16_256MiB_split_sweep(engine):
             assert_same_bits(out, want, "%s units %d" % (w.name, units))
 
 
-def sampled_windows(count, nwin=48, width=1 << 16, seed=5):
+def sampled_windows(count, cuts=(), nwin=48, width=1 << 16, seed=5):
+    """First, last, random windows and one across every cut, clipped to the message."""
+    width = min(width, count)
     rng = np.random.default_rng(seed)
-    starts = [0, count - width] + [int(s) for s in rng.integers(0, count - width, nwin)]
-    return [(s, s + width) for s in starts]
+    starts = [0, count - width] + [int(x) for x in rng.integers(0, count - width + 1, nwin)]
+    starts += [min(max(c - width // 2, 0), count - width) for c in cuts if 0 < c < count]
+    return [(a, a + width) for a in starts]
 
 
-def test_config3_largest_sweep_point_sampled():
-    # 1024 MiB per rank: the oracle checks sampled windows (first, last, random)
-    w = [x for x in wl.sweep_workloads() if x.count == 512 * wl.MIB]
-    ar = [x for x in w if x.collective == "allreduce"][0]
-    say("generating", ar.name)
-    bufs = wl.make_rank_buffers(ar, DEV)
-    with Comm(max_bytes=ar.bytes_per_rank) as comm:
-        out = torch.zeros(ar.count, dtype=ar.dtype, device=DEV)
-        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, 100)
-        fx.flex_allreduce_local(comm, bufs, out)
+class Config3Checker:
+    """Compares an output of a configuration-3 case with the oracle: element by
+    element up to 256 MiB per rank, above that on at least 50 windows (first,
+    last, random, across every cut between two paths' pieces)."""
+
+    def __init__(self, w, bufs):
+        self.w, self.bufs = w, bufs
+        self.is_ar = w.collective == "allreduce"
+        self.full = w.bytes_per_rank <= 256 * wl.MIB
+        if self.full:
+            host = [wl.to_numpy_bits(b) for b in bufs]
+            self.want = oc.allreduce(host) if self.is_ar else oc.allgather(host)
+
+    def check(self, out, cuts, what):
+        n = self.w.count
+        if self.full:
+            if self.is_ar:
+                assert_same_bits(out, self.want, what)
+            else:
+                assert np.array_equal(wl.to_numpy_bits(out), self.want), what
+            return
+        for a, b in sampled_windows(n, cuts):
+            host = [wl.to_numpy_bits(x[a:b]) for x in self.bufs]
+            if self.is_ar:
+                assert_same_bits(out[a:b], oc.allreduce(host), "%s window %d" % (what, a))
+            else:
+                got = torch.cat([out[r * n + a:r * n + b] for r in range(8)])
+                assert np.array_equal(wl.to_numpy_bits(got), oc.allgather(host)), "%s window %d" % (what, a)
+
+
+@pytest.mark.parametrize("mib", wl.SWEEP_MIB_PER_RANK)
+@pytest.mark.parametrize("collective", ["allreduce", "allgather"])
+def test_config3_sweep_point_under_its_own_protocol(collective, mib):
+    # one point of the message-size sweep: Stage 1 on the hardware (rates, InitializeShares,
+    # Algorithm 1, acceptance check), then 20 Stage-2 windows of adaptive calls; the output
+    # is compared with the oracle after tuning and after the last window, every balancer
+    # decision with the oracle balancer fed the same measured times.  If Stage 1 withdrew
+    # the host path, a second leg installs the balanced shares so that three more windows
+    # run with the host path live.
+    w = [x for x in wl.sweep_workloads() if x.collective == collective and x.bytes_per_rank == mib * wl.MIB][0]
+    say("generating", w.name)
+    bufs = wl.make_rank_buffers(w, DEV)
+    is_ar = collective == "allreduce"
+    coll = fx.FLEX_ALLREDUCE if is_ar else fx.FLEX_ALLGATHER
+    checker = Config3Checker(w, bufs)
+    cfg = fx.flex_config_default()
+    window = cfg.balancer.window
+
+    def stats():
+        return fx.flex_get_stats(comm, coll, w.count, w.dtype)
+
+    with Comm(max_bytes=w.bytes_per_rank) as comm:
+        out = torch.zeros(w.count if is_ar else 8 * w.count, dtype=w.dtype, device=DEV)
+
+        def call():
+            if is_ar:
+                fx.flex_allreduce_local(comm, bufs, out)
+            else:
+                fx.flex_allgather_local(comm, bufs, out)
+
+        res = fx.flex_comm_tune(comm, coll, bufs, out)
+        say("tune", w.name, res.as_dict())
         torch.cuda.synchronize()
-        split = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, ar.count, ar.dtype).last_split
-        wins = sampled_windows(ar.count) + [(split - 4096, split + 4096)]
-        for a, b in wins:
-            assert_same_bits(out[a:b], oracle_allreduce([x[a:b] for x in bufs]), "window %d" % a)
-        del out
-        ag_out = torch.zeros(8 * ar.count, dtype=ar.dtype, device=DEV)
-        fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, 100)
-        fx.flex_allgather_local(comm, bufs, ag_out)
-        torch.cuda.synchronize()
-        for r in range(8):
-            for a, b in sampled_windows(ar.count, nwin=8, seed=r) + [(split - 4096, split + 4096)]:
-                assert torch.equal(ag_out[r * ar.count + a:r * ar.count + b].view(torch.int16),
-                                   bufs[r][a:b].view(torch.int16)), (r, a)
+        checker.check(out, [stats().last_split], "after tune")
+        check_stage1_against_oracle(comm, coll, w.count, w.dtype, res, cfg)
+
+        fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
+        twin = Stage2Twin(comm, coll, w.count, w.dtype, cfg)
+        trajectory = []
+        for k in range(20 * window):
+            if k == 20 * window - 1:
+                out.zero_()
+            share = twin.twin.S[1]
+            call()
+            st = twin.after_call()
+            # the cut the call used is the oracle's cut for the share the oracle held
+            assert st.last_split == op.partition(w.count, share, 10000, 2048, (64 << 10) // out.element_size())
+            if k % window == window - 1:
+                trajectory.append(twin.twin.S[1])
+        say("host share after each of 20 windows:", trajectory)
+        checker.check(out, [stats().last_split], "after 20 adaptive windows")
+
+        if trajectory[-1] == 0:
+            # host path withdrawn: run three windows with it live, from the shares Algorithm 1 balanced
+            # at (or the probe share if it drained the path itself)
+            units = res.balanced_shares[1] or res.initial_shares[1] or cfg.probe_units
+            fx.flex_comm_set_shares(comm, coll, w.count, w.dtype, [10000 - units, units])
+            twin = Stage2Twin(comm, coll, w.count, w.dtype, cfg)
+            for k in range(3 * window):
+                if k == 3 * window - 1:
+                    out.zero_()
+                share = twin.twin.S[1]
+                call()
+                st = twin.after_call()
+                assert st.last_split == op.partition(w.count, share, 10000, 2048, (64 << 10) // out.element_size())
+            say("host path live:", units, "->", twin.twin.S[1], "units; times", list(st.last_time_s)[:2])
+            assert st.samples == twin.samples and st.split_calls >= 3 * window
+            checker.check(out, [st.last_split], "host path live, after 3 windows")
 
 
 def test_config4_prefill_allreduce_adaptive_50_calls():
@@ -703,6 +859,7 @@ def test_config4_prefill_allreduce_adaptive_50_calls():
         torch.cuda.synchronize()
         assert_same_bits(out, want, "after tune")
         assert sum(res.shares) == 10000 and res.path_bw[0] > 0
+        check_stage1_against_oracle(comm, fx.FLEX_ALLREDUCE, w.count, w.dtype, res, fx.flex_config_default())
         fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
         outs = [torch.zeros(w.count, dtype=w.dtype, device=DEV) for _ in range(2)]
         for k in range(50):
@@ -731,7 +888,7 @@ def test_tune_then_adaptive_stays_exact_and_balanced():
             res = fx.flex_comm_tune(comm, coll, bufs, out)
             say("tune", coll, res.as_dict())
             assert sum(res.shares) == 10000 and res.iterations <= 100
-            assert res.initial_shares[1] == int(10000 * res.path_bw[1] / (res.path_bw[0] + res.path_bw[1]))
+            check_stage1_against_oracle(comm, coll, count, torch.bfloat16, res, fx.flex_config_default())
             if res.active_mask & 2:
                 t = res.path_time_s
                 # Algorithm 1 stopped either balanced or at the iteration cap
@@ -761,51 +918,127 @@ def test_tune_then_adaptive_stays_exact_and_balanced():
 @pytest.mark.parametrize("engine", ENGINES)
 def test_stage2_runs_on_hardware(engine):
     # explicit shares keep the host path active, so the Evaluator feeds real
-    # per-path times into Stage 2 while calls keep coming
+    # per-path times into Stage 2 while calls keep coming; the oracle's Stage 2,
+    # fed the same times, must hold the same shares after every call
     count = 32 * wl.MIB        # 64 MiB per rank
     bufs = wl.make_rank_buffers(wl.config(1), DEV, count=count)
     want = oracle_allreduce(bufs)
+    cfg = fx.flex_config_default()
     with Comm(max_bytes=count * 2, host_engine=engine) as comm:
         out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
         with pytest.raises(fx.FlexError):
             fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9000, 999])
         fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9900, 100])
         fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
+        twin = Stage2Twin(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, cfg)
         trajectory = [100]
         for k in range(80):
             fx.flex_allreduce_local(comm, bufs, out)
+            st = twin.after_call()
             if k % 10 == 9:
-                torch.cuda.synchronize()
                 assert_same_bits(out, want, "adaptive call %d" % k)
-                fx.flex_evaluator_drain(comm)
-                st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
                 trajectory.append(int(st.balancer.shares[1]))
                 assert sum(st.balancer.shares) == 10000 and st.balancer.stage == fx.FLEX_STAGE_RUNTIME
-        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
-        say("stats", st.as_dict(), trajectory)
+        say("stats", st.as_dict(), trajectory, twin.moves)
         assert st.samples == 80 and st.split_calls == 80
         assert 1 <= st.balancer.adjustments <= 8                # the paths are far from balance at 1 %
-        # every window moves at most one fixed step of 4 units
-        assert all(abs(b - a) in (0, 4) for a, b in zip(trajectory, trajectory[1:]))
-        # samples measured before a share change are not fed into the next window:
-        # a move needs a full window of 10 samples taken at the current shares
-        assert st.balancer.adjustments <= 80 // 10
+        # every window moves at most one fixed step of 4 units, from the slower path to the device path
+        assert all(m in ([4, -4], [-4, 4]) for m in twin.moves)
+        # queued without draining in between, samples taken before a share change are dropped:
+        # a move needs a full window of 10 samples at the current shares
+        fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9900, 100])
+        for k in range(40):
+            fx.flex_allreduce_local(comm, bufs, out)
+        torch.cuda.synchronize()
+        fx.flex_evaluator_drain(comm)
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+        assert st.balancer.adjustments <= 40 // 10 and sum(st.balancer.shares) == 10000
+        assert (10000 - st.balancer.shares[0]) % 4 == 0
+        assert_same_bits(out, want, "queued adaptive calls")
 
 
-def test_tune_acceptance_check_never_leaves_a_slower_split():
+@pytest.mark.parametrize("coll", [fx.FLEX_REDUCESCATTER, fx.FLEX_ALLTOALL])
+def test_tune_and_adaptive_calls_for_reducescatter_and_alltoall(coll):
+    # the two other collectives through Stage 1 and Stage 2, against both oracles
+    n, rank = 8, 5
+    cnt = 4 * wl.MIB + 2048 + 3          # elements per slice / piece: 8 MiB of bf16 and a ragged end
+    dtype = torch.bfloat16
+    bufs = [wl.random_bits(n * cnt, dtype, 300 + r, DEV, finite_only=True) for r in range(n)]
+    bufs = [torch.ldexp(torch.frexp(b.float())[0], torch.tensor(r % 3, device=DEV)).to(dtype) for r, b in enumerate(bufs)]
+    host = [wl.to_numpy_bits(b) for b in bufs]
+    is_rs = coll == fx.FLEX_REDUCESCATTER
+    want = oc.reducescatter(host, rank) if is_rs else oc.alltoall(host, rank)
+    cfg = fx.flex_config_default()
+    with Comm(rank=rank, max_bytes=n * cnt * 2) as comm:
+        out = torch.zeros(cnt if is_rs else n * cnt, dtype=dtype, device=DEV)
+
+        def call():
+            if is_rs:
+                fx.flex_reducescatter_local(comm, bufs, out, recv_count=cnt)
+            else:
+                fx.flex_alltoall_local(comm, bufs, out, count=cnt)
+
+        def check(what):
+            if is_rs:
+                assert_same_bits(out, want, what)
+            else:
+                assert np.array_equal(wl.to_numpy_bits(out), want), what
+
+        res = fx.flex_comm_tune(comm, coll, bufs, out, count=cnt)
+        say("tune", coll, res.as_dict())
+        torch.cuda.synchronize()
+        check("after tune")
+        check_stage1_against_oracle(comm, coll, cnt, dtype, res, cfg)
+        fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
+        twin = Stage2Twin(comm, coll, cnt, dtype, cfg)
+        for k in range(20):
+            out.zero_()
+            call()
+            twin.after_call()
+        check("adaptive, tuned shares")
+        # and with the host path kept live
+        fx.flex_comm_set_shares(comm, coll, cnt, dtype, [9850, 150])
+        twin = Stage2Twin(comm, coll, cnt, dtype, cfg)
+        for k in range(30):
+            out.zero_()
+            share = twin.twin.S[1]
+            call()
+            st = twin.after_call()
+            assert st.last_split == op.partition(cnt, share, 10000, 2048, 32768)
+        check("adaptive, host path live")
+        assert st.samples >= 30 and st.last_time_s[1] > 0
+
+
+def test_tune_acceptance_check_needs_a_gain_beyond_the_noise():
     count = 64 * wl.MIB        # 128 MiB per rank
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    cfg = fx.flex_config_default()
     with Comm(max_bytes=count * 2) as comm:
         out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
         res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
         say("tune", res.as_dict())
-        if res.reverted:
-            assert list(res.shares)[:2] == [10000, 0] and res.active_mask == 1
-            assert res.combined_s >= res.device_alone_s > 0 and res.balanced_shares[1] > 0
-        elif res.active_mask & 2:
-            assert res.combined_s < res.device_alone_s
+        check_stage1_against_oracle(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, res, cfg)
+        if res.balanced_shares[1] > 0:
+            # Algorithm 1 left the host path active: the check ran, interleaved
+            assert res.accept_samples == cfg.accept_pairs * cfg.tune_reps
+            assert res.combined_s > 0 and res.device_alone_s > 0
+            gain = res.device_alone_s - res.combined_s
+            noise = 3 * max(res.combined_mad_s, res.device_alone_mad_s)
+            if res.reverted:
+                assert not gain > noise
+                assert list(res.shares)[:2] == [10000, 0] and res.active_mask == 1
+            else:
+                assert gain > noise and res.active_mask == 3 and res.shares[1] == res.balanced_shares[1]
+        else:
+            assert res.accept_samples == 0 and not res.reverted
         torch.cuda.synchronize()
         assert_same_bits(out, oracle_allreduce(bufs), "after tune")
+    # switched off, the balanced split is kept whatever it costs
+    with Comm(max_bytes=count * 2, tune_accept_check=0) as comm:
+        res = fx.flex_comm_tune(comm, fx.FLEX_ALLREDUCE, bufs, out)
+        assert not res.reverted and res.accept_samples == 0 and list(res.shares) == list(res.balanced_shares)
+        torch.cuda.synchronize()
+        assert_same_bits(out, oracle_allreduce(bufs), "after tune without the check")
 
 
 # ------------------------------------------------------------ error handling

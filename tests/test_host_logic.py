@@ -31,14 +31,17 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_defaults_come_through():
     c = fx.flex_config_default()
+    import ctypes
+    assert c.struct_size == ctypes.sizeof(fx.Config)
     assert c.chunk_bytes == 4 << 20 and c.num_slots == 2 and c.max_host_units == 2500
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
-    assert (c.host_engine, c.host_blocks, c.pipeline_depth, c.min_step_bytes) == (0, 16, 4, 256 << 10)
-    assert c.tune_accept_check == 1 and c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
+    assert (c.host_engine, c.host_blocks, c.min_step_bytes) == (fx.FLEX_ENGINE_HYBRID, 8, 256 << 10)
+    assert c.tune_accept_check == 1 and c.accept_pairs == 3 and c.launch_shape == fx.FLEX_SHAPE_WAVE
+    assert c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
     b = c.balancer
     assert (b.share_total, b.initial_step, b.stability_required, b.max_tune_iters, b.window,
-            b.runtime_step) == (10000, 64, 3, 100, 10, 4)
+            b.runtime_step, b.aux_share_cap) == (10000, 64, 3, 100, 10, 4, 0)
     assert b.convergence_threshold == 0.05 and b.runtime_threshold == 0.10
     assert fx.flex_status_string(0) == "ok" and fx.flex_status_string(1) == "invalid argument"
 
@@ -79,9 +82,10 @@ def test_library_follows_hand_trace():
 
 
 @given(seed=st.integers(0, 10 ** 6), npaths=st.integers(2, 4), step0=st.sampled_from([1, 16, 64, 500]),
-       thr=st.sampled_from([0.01, 0.05, 0.3]), stab=st.integers(1, 4))
-@settings(max_examples=300, deadline=None)
-def test_library_stage1_equals_oracle_step_for_step(seed, npaths, step0, thr, stab):
+       thr=st.sampled_from([0.01, 0.05, 0.3]), stab=st.integers(1, 4), cap=st.sampled_from([0, 0, 2500, 4000]))
+@settings(max_examples=400, deadline=None)
+def test_library_stage1_equals_oracle_step_for_step(seed, npaths, step0, thr, stab, cap):
+    # cap: ceiling on every auxiliary path's share (0 = the paper's method unchanged)
     rnd = random.Random(seed)
     total = 10000
     cuts = sorted(rnd.randint(0, total) for _ in range(npaths - 1))
@@ -101,9 +105,10 @@ def test_library_stage1_equals_oracle_step_for_step(seed, npaths, step0, thr, st
 
     trace = []
     S_or, A_or = ob.initial_tune(S0, make_measure(), step0=step0, threshold=thr, stability_required=stab,
-                                 trace=trace)
+                                 trace=trace, cap=[None] + [cap] * (npaths - 1) if cap else None)
     traj, final = run_library_tune(S0, make_measure(),
-                                   cfg(initial_step=step0, convergence_threshold=thr, stability_required=stab))
+                                   cfg(initial_step=step0, convergence_threshold=thr, stability_required=stab,
+                                       aux_share_cap=cap))
     assert len(traj) == len(trace)
     for a, b in zip(traj, trace):
         assert a["S"] == b["S"] and a["step"] == b["step"] and a["active"] == b["active"]
@@ -128,18 +133,19 @@ def test_library_initialize_shares_equals_oracle(bw, total):
 
 
 @given(seed=st.integers(0, 10 ** 6), npaths=st.integers(2, 4), window=st.sampled_from([1, 2, 5, 10]),
-       step=st.sampled_from([1, 4, 50]))
-@settings(max_examples=200, deadline=None)
-def test_library_stage2_equals_oracle(seed, npaths, window, step):
+       step=st.sampled_from([1, 4, 50]), cap=st.sampled_from([0, 0, 120, 400]))
+@settings(max_examples=300, deadline=None)
+def test_library_stage2_equals_oracle(seed, npaths, window, step, cap):
     rnd = random.Random(seed)
     total = 10000
     cuts = sorted(rnd.randint(0, 300) for _ in range(npaths - 1))
     S0 = [cuts[0]] + [b - a for a, b in zip(cuts, cuts[1:])] if npaths > 1 else []
     S0 = [total - sum(S0)] + S0
-    c = cfg(window=window, runtime_step=step, runtime_threshold=0.10)
+    c = cfg(window=window, runtime_step=step, runtime_threshold=0.10, aux_share_cap=cap)
     b = fx.flex_balancer_init_shares(S0, c)
     fx.flex_balancer_finish_tuning(b)
-    r = ob.RuntimeAdjuster(S0, {p for p in range(npaths) if S0[p] > 0}, window=window, threshold=0.10, step=step)
+    r = ob.RuntimeAdjuster(S0, {p for p in range(npaths) if S0[p] > 0}, window=window, threshold=0.10, step=step,
+                           cap=[None] + [cap] * (npaths - 1) if cap else None)
     try:
         for _ in range(120):
             T = [rnd.choice([1.0, 1.05, 1.2, 3.0, 0.5]) * rnd.uniform(0.9, 1.1) for _ in range(npaths)]
@@ -223,7 +229,8 @@ def test_library_partition_paths_rejects_bad_input():
 
 def test_binding_structs_have_the_library_layout():
     import ctypes
-    want = [ctypes.sizeof(t) for t in (fx.BalancerCfg, fx.BalancerState, fx.Config, fx.Stats, fx.TuneResult)]
+    want = [ctypes.sizeof(t) for t in (fx.BalancerCfg, fx.BalancerState, fx.Config, fx.Stats, fx.TuneResult,
+                                       fx.TuneRound)]
     assert fx.flex_struct_sizes() == want
 
 
@@ -235,8 +242,9 @@ def test_header_is_plain_c_and_its_structs_have_the_library_layout(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include "flexlink.h"\n#include <stdio.h>\n'
-        'int main(void) { printf("%zu %zu %zu %zu %zu\\n", sizeof(flex_balancer_cfg_t), '
-        'sizeof(flex_balancer_state_t), sizeof(flex_config_t), sizeof(flex_stats_t), sizeof(flex_tune_result_t)); '
+        'int main(void) { printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(flex_balancer_cfg_t), '
+        'sizeof(flex_balancer_state_t), sizeof(flex_config_t), sizeof(flex_stats_t), sizeof(flex_tune_result_t), '
+        'sizeof(flex_tune_round_t)); '
         'return (FLEX_MAX_RANKS == 8 && FLEX_MAX_PATHS == 4 && FLEX_ALLTOALL == 3) ? 0 : 1; }\n')
     exe = tmp_path / "sizes"
     inc = os.path.join(ROOT, "include")
@@ -247,6 +255,45 @@ def test_header_is_plain_c_and_its_structs_have_the_library_layout(tmp_path):
     cpp = tmp_path / "only_header.cpp"
     cpp.write_text('#include "flexlink.h"\nint main() { return sizeof(flex_config_t) ? 0 : 1; }\n')
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
+
+
+@given(nbytes=st.integers(0, 1 << 33), chunk=st.sampled_from([4096, 64 << 10, 1 << 20, 4 << 20]),
+       min_step=st.sampled_from([1, 256, 4096, 256 << 10, 8 << 20]), es=st.sampled_from([1, 2, 4]))
+@settings(max_examples=400, deadline=None)
+def test_pipeline_plan_properties(nbytes, chunk, min_step, es):
+    nbytes -= nbytes % es
+    steps = fx.flex_pipeline_plan(nbytes, chunk, min_step)
+    assert sum(steps) == nbytes and all(0 < n <= chunk for n in steps)
+    assert all(n % 256 == 0 for n in steps[:-1])          # only the last step is ragged ...
+    assert all(n % es == 0 for n in steps)                # ... and every step holds whole elements
+    if nbytes >= 256:
+        floor = min(max((min_step + 255) // 256 * 256, 256), chunk)
+        # first and last steps are short (one min_step, give or take the left-overs), the middle ones long
+        if nbytes >= 4 * floor and floor < chunk:
+            assert steps[0] == floor and steps[-1] < 2 * floor + 256
+        assert len(steps) <= nbytes // chunk + 2 * 16 + 2
+    # the ramps mirror each other: as many doubling steps at the front as halving steps at the back
+    up = 0
+    while up + 1 < len(steps) and steps[up + 1] == 2 * steps[up] and steps[up + 1] < chunk:
+        up += 1
+    if up:
+        back = steps[::-1]
+        back[0] -= back[0] % 256 if back[0] >= 256 else 0       # the last step also carries the left-over bytes
+        assert back[:up] == steps[:up]
+
+
+def test_pipeline_plan_hand_values_and_errors():
+    K = 1 << 10
+    assert fx.flex_pipeline_plan(0) == []
+    assert fx.flex_pipeline_plan(100) == [100]
+    assert fx.flex_pipeline_plan(1 << 20) == [256 * K, 512 * K, 256 * K]
+    assert fx.flex_pipeline_plan(10 << 20) == [x * K for x in (256, 512, 1024, 2048, 2560, 2048, 1024, 512, 256)]
+    assert fx.flex_pipeline_plan((1 << 20) + 6) == [256 * K, 512 * K, 256 * K + 6]
+    assert fx.flex_pipeline_plan(9 << 20, 4 << 20, 4 << 20) == [3 << 20] * 3     # no ramp: even steps
+    with pytest.raises(fx.FlexError):
+        fx.flex_pipeline_plan(1 << 20, 1000, 256)
+    with pytest.raises(fx.FlexError):
+        fx.flex_pipeline_plan(1 << 20, 4096, 0)
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
