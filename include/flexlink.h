@@ -242,7 +242,8 @@ typedef struct flex_config {
     uint32_t struct_size;        /* sizeof(flex_config_t) as the caller's header declares it.
                                     flex_config_default() fills it in; flex_comm_create() refuses any other
                                     value, so a caller built against another layout fails loudly */
-    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering */
+    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering; default 3, which
+                                    also hides the hand-off between a DMA copy and the kernel behind it */
     uint64_t chunk_bytes;        /* transit buffer bytes per peer and pipeline step (paper: 4 MB; default
                                     4 MiB); one pinned slot holds (nranks-1) * chunk_bytes */
     uint64_t min_split_bytes;    /* messages shorter than this per rank are never split (default 64 KiB) */

@@ -150,21 +150,30 @@ struct HostPath {
     // how often each slot has been used so far
     std::vector<uint64_t*> sem_full, sem_empty;
     std::vector<uint64_t> slot_uses;
+    // hybrid engine with event hand-over: one in-order stream ("lane") per
+    // slot that runs a step from start to end - copy kernel, DMA copy, finishing
+    // kernel - so that no DMA copy ever has a cross-stream wait or another DMA
+    // copy in front of it (either costs tens of microseconds of hand-off on this
+    // runtime, a kernel in front of it does not)
+    std::vector<hipStream_t> lane;
+    std::vector<hipEvent_t> ev_up, ev_end;
+    hipStream_t tail = nullptr;  // stream the last call's final step ended on
     uint64_t chunk_seq = 0;  // steps staged since creation; slot = seq % num_slots
     char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
     size_t scratch_stride = 0;
 
-    hipStream_t last_stream() const { return engine == FLEX_ENGINE_HYBRID ? s_fin : s_down; }
+    bool lanes() const { return !lane.empty(); }
+    hipStream_t last_stream() const { return lanes() ? tail : engine == FLEX_ENGINE_HYBRID ? s_fin : s_down; }
 
     void quiesce() {
-        if (s_up) (void)hipStreamSynchronize(s_up);
-        if (s_down) (void)hipStreamSynchronize(s_down);
-        if (s_fin) (void)hipStreamSynchronize(s_fin);
+        for (hipStream_t st : {s_up, s_down, s_fin})
+            if (st) (void)hipStreamSynchronize(st);
+        for (hipStream_t st : lane) (void)hipStreamSynchronize(st);
     }
 
     void destroy() {
         quiesce();
-        for (auto* vec : {&ev_full, &ev_empty, &ev_staged, &ev_stage_free})
+        for (auto* vec : {&ev_full, &ev_empty, &ev_staged, &ev_stage_free, &ev_up, &ev_end})
             for (auto e : *vec) (void)hipEventDestroy(e);
         for (auto p : sem_full) (void)hipFree(p);
         for (auto p : sem_empty) (void)hipFree(p);
@@ -173,6 +182,7 @@ struct HostPath {
         if (scratch) (void)hipFree(scratch);
         for (hipStream_t st : {s_up, s_down, s_fin})
             if (st) (void)hipStreamDestroy(st);
+        for (hipStream_t st : lane) (void)hipStreamDestroy(st);
         *this = HostPath();
     }
 };
@@ -209,7 +219,9 @@ struct flex_comm {
     // In a slot the peers' pieces lie back to back (stride = the step's size
     // rounded up to 256 bytes), so the hybrid engine brings a whole step back
     // with one DMA copy.
-    int host_path(HostPath& hp, const HostJob& job, size_t bytes) {
+    int host_path(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
+        if (hp.lanes()) return host_path_lanes(hp, job, bytes, fork);
+        HIP_TRY(hipStreamWaitEvent(hp.s_up, fork, 0));
         const size_t nslots = hp.pinned.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
         const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
@@ -322,6 +334,79 @@ struct flex_comm {
                 in[r] = (r == job.local_index) ? (const void*)job.local_src : (const void*)job.peer_dst[j++];
             LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part, bytes / es, job.dtype, reduce_shape,
                                              hp.s_down));
+        }
+        return FLEX_OK;
+    }
+
+    // The same for the hybrid engine with event hand-over.  Step k runs from
+    // start to end on lane k mod L, an in-order stream with its own pinned slot
+    // and staging buffer: copy kernel (device -> pinned slot), DMA copy (pinned
+    // slot -> staging buffer), finishing kernel (reduce, or place the pieces).
+    // Stream order alone protects the slot and the staging buffer.  The copy
+    // kernels of successive steps are chained by events, so that they follow one
+    // another on the upstream direction of the link while the DMA copies of
+    // earlier steps occupy the downstream one; with three lanes the hand-off
+    // between a DMA copy and the kernel behind it is hidden as well.
+    int host_path_lanes(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
+        const size_t L = hp.lane.size();
+        const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
+        const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
+        if (steps.empty()) {
+            hp.tail = hp.lane[0];
+            HIP_TRY(hipStreamWaitEvent(hp.tail, fork, 0));
+            return FLEX_OK;
+        }
+        bool used[64] = {false};
+        size_t off = 0, prev = L;  // prev: lane of the step before (L = none yet)
+        for (const uint64_t n : steps) {
+            const size_t l = hp.chunk_seq % L;
+            hipStream_t st = hp.lane[l];
+            const size_t stride = (n + 255) / 256 * 256;
+            char* base = (char*)hp.pinned[l];
+            char* stage = hp.stage[l];
+            if (!used[l]) {
+                HIP_TRY(hipStreamWaitEvent(st, fork, 0));
+                used[l] = true;
+            }
+            if (prev != L && prev != l) HIP_TRY(hipStreamWaitEvent(st, hp.ev_up[prev], 0));
+            const void* up_src[FLEX_MAX_RANKS];
+            void* up_dst[FLEX_MAX_RANKS];
+            uint64_t nn[FLEX_MAX_RANKS];
+            for (int j = 0; j < job.npeers; ++j) {
+                up_src[j] = job.peer_src[j] + off;
+                up_dst[j] = base + (size_t)j * stride;
+                nn[j] = n;
+            }
+            LAUNCH_TRY(flex::launch_gather_copy(up_src, up_dst, nn, job.npeers, link_copy_shape, st));
+            HIP_TRY(hipEventRecord(hp.ev_up[l], st));
+            HIP_TRY(hipMemcpyAsync(stage, base, (size_t)(job.npeers - 1) * stride + n, hipMemcpyHostToDevice, st));
+            if (job.reduce) {
+                const void* in[FLEX_MAX_RANKS];
+                int j = 0;
+                for (int r = 0; r < job.nranks; ++r)
+                    in[r] = (r == job.local_index) ? (const void*)(job.local_src + off)
+                                                   : (const void*)(stage + (size_t)(j++) * stride);
+                LAUNCH_TRY(flex::launch_reduce_n(in, job.nranks, job.out_part + off, n / es, job.dtype,
+                                                 stage_reduce_shape, st));
+            } else {
+                const void* dn_src[FLEX_MAX_RANKS];
+                void* dn_dst[FLEX_MAX_RANKS];
+                for (int j = 0; j < job.npeers; ++j) {
+                    dn_src[j] = stage + (size_t)j * stride;
+                    dn_dst[j] = job.peer_dst[j] + off;
+                }
+                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, stage_copy_shape, st));
+            }
+            prev = l;
+            ++hp.chunk_seq;
+            off += n;
+        }
+        // the lane of the last step collects the others: the path is done when it is
+        hp.tail = hp.lane[prev];
+        for (size_t l = 0; l < L; ++l) {
+            if (!used[l] || l == prev) continue;
+            HIP_TRY(hipEventRecord(hp.ev_end[l], hp.lane[l]));
+            HIP_TRY(hipStreamWaitEvent(hp.tail, hp.ev_end[l], 0));
         }
         return FLEX_OK;
     }
@@ -584,7 +669,6 @@ int flex_comm::split_reduce(TimingRecord* rec, const uint64_t* start, const void
         const uint64_t lo = start[a + 1], hi = start[a + 2];
         if (hi == lo) continue;
         HostPath& hp = aux[a];
-        HIP_TRY(hipStreamWaitEvent(hp.s_up, rec->fork, 0));
         HostJob job;
         job.reduce = true;
         job.dtype = dtype;
@@ -598,7 +682,7 @@ int flex_comm::split_reduce(TimingRecord* rec, const uint64_t* start, const void
             job.peer_dst[job.npeers] = hp.scratch ? hp.scratch + (size_t)job.npeers * hp.scratch_stride : nullptr;
             ++job.npeers;
         }
-        int st = host_path(hp, job, (hi - lo) * es);
+        int st = host_path(hp, job, (hi - lo) * es, rec->fork);
         if (st) return st;
         HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
         rec->used_mask |= 1u << (a + 1);
@@ -674,7 +758,6 @@ int flex_comm::split_gather(TimingRecord* rec, const uint64_t* start, const void
         const uint64_t lo = start[a + 1], hi = start[a + 2];
         if (hi == lo) continue;
         HostPath& hp = aux[a];
-        HIP_TRY(hipStreamWaitEvent(hp.s_up, rec->fork, 0));
         HostJob job;
         for (int r = 0; r < nranks; ++r) {
             if (r == rank) continue;
@@ -682,7 +765,7 @@ int flex_comm::split_gather(TimingRecord* rec, const uint64_t* start, const void
             job.peer_dst[job.npeers] = (char*)dst[r] + lo * es;
             ++job.npeers;
         }
-        int st = host_path(hp, job, (hi - lo) * es);
+        int st = host_path(hp, job, (hi - lo) * es, rec->fork);
         if (st) return st;
         HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
         rec->used_mask |= 1u << (a + 1);
@@ -744,7 +827,7 @@ int flex_config_default(flex_config_t* cfg) {
     memset(cfg, 0, sizeof *cfg);
     cfg->struct_size = (uint32_t)sizeof *cfg;
     cfg->chunk_bytes = 4u << 20;
-    cfg->num_slots = 2;
+    cfg->num_slots = 3;
     cfg->max_host_units = 2500;
     cfg->split_align_elems = 2048;
     cfg->min_split_bytes = 64u << 10;
@@ -865,10 +948,24 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
             // the first auxiliary path uses the configured engine, the second the next one
             hp.engine = (int)((c.host_engine + (uint32_t)a) % 3u);
             // side streams at the default priority
-            CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
-            CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
-            if (hp.engine == FLEX_ENGINE_HYBRID) CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
+            const bool lanes = hp.engine == FLEX_ENGINE_HYBRID && c.slot_sync == FLEX_SYNC_EVENTS;
+            if (!lanes) {
+                CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
+                CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
+                if (hp.engine == FLEX_ENGINE_HYBRID)
+                    CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
+            }
             for (uint32_t s = 0; s < c.num_slots; ++s) {
+                if (lanes) {
+                    hipStream_t st = nullptr;
+                    CREATE_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+                    hp.lane.push_back(st);
+                    for (auto* vec : {&hp.ev_up, &hp.ev_end}) {
+                        hipEvent_t e = nullptr;
+                        CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                        vec->push_back(e);
+                    }
+                }
                 void* p = nullptr;
                 CREATE_TRY(hipHostMalloc(&p, slot_bytes, hipHostMallocDefault));
                 hp.pinned.push_back(p);

@@ -33,7 +33,7 @@ def test_struct_layout_defaults_come_through():
     c = fx.flex_config_default()
     import ctypes
     assert c.struct_size == ctypes.sizeof(fx.Config)
-    assert c.chunk_bytes == 4 << 20 and c.num_slots == 2 and c.max_host_units == 2500
+    assert c.chunk_bytes == 4 << 20 and c.num_slots == 3 and c.max_host_units == 2500
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
     assert (c.host_engine, c.host_blocks, c.min_step_bytes) == (fx.FLEX_ENGINE_HYBRID, 8, 256 << 10)
