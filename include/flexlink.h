@@ -414,6 +414,33 @@ int flex_reducescatter_local(flex_comm_t* comm, const void* const* rank_bufs, vo
 int flex_allgather_local(flex_comm_t* comm, const void* const* rank_slices, void* out,
                          size_t slice_count, int dtype, void* hip_stream);
 
+/* AllReduce(sum), local share, for callers that cannot allocate: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No
+ * communicator is needed and the call allocates nothing, on the host or on the
+ * device, and creates no stream or event.
+ *   rank_bufs, out, count, dtype, op, hip_stream  as for flex_allreduce_local;
+ *   nranks, rank   as for flex_comm_create;
+ *   staged_units   share of the message, in units of 1/10000, whose peer parts
+ *                  are staged through a transit buffer before they are reduced
+ *                  (0 = none: one kernel launch).
+ * The message is cut as flex_allreduce_local cuts it at its default settings;
+ * the head is reduced straight from the rank buffers, the tail's peer parts are
+ * first copied into a transit buffer and reduced from there in the same rank
+ * order, with the local rank's part read in place.  The result has the bits of
+ * flex_allreduce_local.  Everything is enqueued on hip_stream, so a call may be
+ * captured into a graph (make the first call on each device outside a capture:
+ * it looks the transit buffer's address up once per device).
+ * The transit buffer is a 32 MiB array built into the library's device code;
+ * each GPU the library runs on holds it until the process ends.  The staged
+ * part, rounded up to 256 bytes, times (nranks - 1) must fit into it
+ * (4 MiB per peer with 8 ranks); a larger one is refused with INVALID_ARG and
+ * nothing is enqueued.  All calls on one GPU share the buffer: calls that may
+ * run at the same time on different streams of one GPU race on it.  Nothing in
+ * it needs clearing between calls (a call reads only what it has just written).
+ * Errors: INVALID_ARG, UNSUPPORTED (dtype, op, device index above 63), HIP. */
+int flex_allreduce_staged_noalloc(const void* const* rank_bufs, int nranks, int rank, void* out, size_t count,
+                                  int dtype, int op, uint32_t staged_units, void* hip_stream);
+
 /* AllToAll, local share: the primitive the paper names as its next one
  * (Limitations and Future Work).
  *   rank_bufs  host array of nranks device pointers; rank_bufs[r] holds rank r's

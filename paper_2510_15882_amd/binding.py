@@ -130,6 +130,7 @@ def lib():
         "flex_allgather_local": [vp, pvp, vp, sz, ci, vp],
         "flex_reducescatter_local": [vp, pvp, vp, sz, ci, ci, vp],
         "flex_alltoall_local": [vp, pvp, vp, sz, ci, vp],
+        "flex_allreduce_staged_noalloc": [pvp, ci, ci, vp, sz, ci, ci, u32, vp],
         "flex_set_split": [vp, ci, ci, u32],
         "flex_comm_tune": [vp, ci, pvp, vp, sz, ci, vp, P(TuneResult)],
         "flex_comm_set_shares": [vp, ci, sz, ci, P(u32)],
@@ -285,6 +286,14 @@ def flex_allreduce_local(comm, rank_bufs, out, count=None, op=FLEX_SUM, stream=N
     count = rank_bufs[0].numel() if count is None else count
     _check(lib().flex_allreduce_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
                                       dtype_code(out.dtype), op, _stream_handle(stream)))
+
+
+def flex_allreduce_staged_noalloc(rank_bufs, rank, out, count=None, staged_units=0, op=FLEX_SUM, stream=None):
+    """No communicator: the staged part goes through the library's built-in transit buffer."""
+    _check_tensors(rank_bufs, out)
+    count = rank_bufs[0].numel() if count is None else count
+    _check(lib().flex_allreduce_staged_noalloc(_pointer_array(rank_bufs), len(rank_bufs), rank, out.data_ptr(), count,
+                                               dtype_code(out.dtype), op, staged_units, _stream_handle(stream)))
 
 
 def flex_reducescatter_local(comm, rank_bufs, out, recv_count=None, op=FLEX_SUM, stream=None):

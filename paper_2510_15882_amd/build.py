@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflexlink.so")
 
-SOURCES = ["balancer.cpp", "comm.cpp", "reduce_n.hip", "gather_copy.hip"]
+SOURCES = ["balancer.cpp", "comm.cpp", "reduce_n.hip", "gather_copy.hip", "noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
