@@ -209,17 +209,20 @@ int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint
  * Communicator (paper: Section "Communicator").
  * ---------------------------------------------------------------------- */
 enum flex_host_engine {
-    FLEX_ENGINE_HYBRID = 0, /* default.  Producer stage: one small copy kernel writes all peers' pieces into
-                               the pinned slot over PCIe; consumer stage: one hipMemcpyAsync (DMA engine)
-                               brings the slot back into a device staging buffer, and a kernel on a third
-                               stream reduces from there (AllReduce) or places the pieces (AllGather).
-                               On MI355X this is the pairing that keeps both PCIe directions busy: a DMA
-                               engine writes host memory at half the rate of a copy kernel, and a kernel
-                               reading host memory is starved by the producer's writes. */
-    FLEX_ENGINE_KERNEL = 1, /* both stages are small HIP kernels that write to / read from the pinned buffer
+    FLEX_ENGINE_AUTO = 0,   /* default: FLEX_ENGINE_KERNEL for host parts shorter than hybrid_min_bytes per
+                               peer (lowest latency: about 55 us for the first byte against 180 us),
+                               FLEX_ENGINE_HYBRID for longer ones (highest rate, no compute units held while
+                               the data comes back).  With FLEX_SYNC_COUNTERS it is FLEX_ENGINE_KERNEL. */
+    FLEX_ENGINE_HYBRID = 1, /* Producer stage: one small copy kernel writes all peers' pieces into the pinned
+                               slot over PCIe; consumer stage: one hipMemcpyAsync (DMA engine) brings the slot
+                               back into a device staging buffer, and a kernel reduces from there (AllReduce)
+                               or places the pieces (AllGather).  On MI355X a DMA engine writes host memory
+                               at half the rate of a copy kernel, and a kernel that reads host memory
+                               competes with the producer's writes for the same request queues. */
+    FLEX_ENGINE_KERNEL = 2, /* both stages are small HIP kernels that write to / read from the pinned buffer
                                over PCIe; for AllReduce the second stage is the reduce kernel itself, reading
                                the peers straight from pinned memory */
-    FLEX_ENGINE_SDMA = 2    /* both stages are hipMemcpyAsync copies (DMA engines), one per peer and step;
+    FLEX_ENGINE_SDMA = 3    /* both stages are hipMemcpyAsync copies (DMA engines), one per peer and step;
                                AllReduce then reduces once from a device scratch buffer */
 };
 
@@ -266,10 +269,10 @@ typedef struct flex_config {
                                     3 (default) non-temporal loads and stores.  Plain stores let a reused
                                     output stay in the 256 MB memory-side cache (an nccl-tests style loop) */
     uint32_t copy_nontemporal;   /* same for the copy kernel */
-    uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_HYBRID; the
-                                    benchmark target's hipMemcpyAsync-both-ways engine is FLEX_ENGINE_SDMA) */
-    uint32_t host_blocks;        /* workgroups (of 256 threads) each host-path kernel that touches pinned
-                                    memory may occupy (default 8: two already fill the link) */
+    uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_AUTO; the
+                                    engine with hipMemcpyAsync in both directions is FLEX_ENGINE_SDMA) */
+    uint32_t host_blocks;        /* workgroups (of 256 threads) of the producer-stage copy kernel, which writes
+                                    pinned memory (default 8: two already fill the link) */
     uint32_t host_die_shift;     /* 0 = host-path workgroups spread over all 8 accelerator dies; 1..3 = their
                                     grids are 2^shift times larger and only every 2^shift-th workgroup works,
                                     which keeps them on 4, 2 (default) or 1 of the dies and disturbs the device
@@ -279,8 +282,13 @@ typedef struct flex_config {
                                     that little of it travels with only one of the two stages busy */
     uint32_t slot_sync;          /* flex_slot_sync (default FLEX_SYNC_EVENTS) */
     uint32_t num_aux_paths;      /* host-staged paths: 1 (default) = FLEX_PATH_HOST with host_engine;
-                                    2 = also FLEX_PATH_HOST2 with the next engine in the enum's cyclic order */
-    uint32_t reserved[2];
+                                    2 = also FLEX_PATH_HOST2 on FLEX_ENGINE_SDMA (on FLEX_ENGINE_KERNEL if the
+                                    first one is FLEX_ENGINE_SDMA) */
+    uint32_t host_down_blocks;   /* FLEX_ENGINE_KERNEL: workgroups of the consumer-stage kernel, which reads
+                                    pinned memory (default 6; measured on MI355X next to 8 producer workgroups:
+                                    4 give 34.7, 6 give 41.9, 8 give 38.2, 16 give 31 GB/s each way) */
+    uint32_t hybrid_min_bytes;   /* FLEX_ENGINE_AUTO: host parts of at least this many bytes per peer take
+                                    FLEX_ENGINE_HYBRID (default 4 MiB) */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

@@ -158,12 +158,20 @@ struct HostPath {
     std::vector<hipStream_t> lane;
     std::vector<hipEvent_t> ev_up, ev_end;
     hipStream_t tail = nullptr;  // stream the last call's final step ended on
+    // FLEX_ENGINE_AUTO uses the lanes for long host parts and the two-stream
+    // pipeline for short ones; both work on the same pinned slots, so a call that
+    // changes over first waits for the end of the call before it
+    hipEvent_t ev_path_end = nullptr;
+    int last_way = 0;            // 0 = nothing yet, 1 = two-stream pipeline, 2 = lanes
+    int call_engine = FLEX_ENGINE_KERNEL;  // engine of the call being enqueued
     uint64_t chunk_seq = 0;  // steps staged since creation; slot = seq % num_slots
     char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
     size_t scratch_stride = 0;
 
-    bool lanes() const { return !lane.empty(); }
-    hipStream_t last_stream() const { return lanes() ? tail : engine == FLEX_ENGINE_HYBRID ? s_fin : s_down; }
+    bool on_lanes() const { return call_engine == FLEX_ENGINE_HYBRID && !lane.empty(); }
+    hipStream_t last_stream() const {
+        return on_lanes() ? tail : call_engine == FLEX_ENGINE_HYBRID ? s_fin : s_down;
+    }
 
     void quiesce() {
         for (hipStream_t st : {s_up, s_down, s_fin})
@@ -183,6 +191,7 @@ struct HostPath {
         for (hipStream_t st : {s_up, s_down, s_fin})
             if (st) (void)hipStreamDestroy(st);
         for (hipStream_t st : lane) (void)hipStreamDestroy(st);
+        if (ev_path_end) (void)hipEventDestroy(ev_path_end);
         *this = HostPath();
     }
 };
@@ -220,12 +229,27 @@ struct flex_comm {
     // rounded up to 256 bytes), so the hybrid engine brings a whole step back
     // with one DMA copy.
     int host_path(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
-        if (hp.lanes()) return host_path_lanes(hp, job, bytes, fork);
+        hp.call_engine = hp.engine;
+        if (hp.engine == FLEX_ENGINE_AUTO)
+            hp.call_engine = (!hp.lane.empty() && bytes >= cfg.hybrid_min_bytes) ? FLEX_ENGINE_HYBRID
+                                                                                 : FLEX_ENGINE_KERNEL;
+        const int way = hp.on_lanes() ? 2 : 1;
+        const bool changeover = hp.last_way != 0 && hp.last_way != way;
+        hp.last_way = way;
+        int st = way == 2 ? host_path_lanes(hp, job, bytes, fork, changeover)
+                          : host_path_pipeline(hp, job, bytes, fork, changeover);
+        if (st) return st;
+        HIP_TRY(hipEventRecord(hp.ev_path_end, hp.last_stream()));
+        return FLEX_OK;
+    }
+
+    int host_path_pipeline(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork, bool changeover) {
         HIP_TRY(hipStreamWaitEvent(hp.s_up, fork, 0));
+        if (changeover) HIP_TRY(hipStreamWaitEvent(hp.s_up, hp.ev_path_end, 0));
         const size_t nslots = hp.pinned.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
         const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
-        const int engine = hp.engine;
+        const int engine = hp.call_engine;
         const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
 
         size_t off = 0;
@@ -347,7 +371,7 @@ struct flex_comm {
     // another on the upstream direction of the link while the DMA copies of
     // earlier steps occupy the downstream one; with three lanes the hand-off
     // between a DMA copy and the kernel behind it is hidden as well.
-    int host_path_lanes(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
+    int host_path_lanes(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork, bool changeover) {
         const size_t L = hp.lane.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
         const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
@@ -366,6 +390,7 @@ struct flex_comm {
             char* stage = hp.stage[l];
             if (!used[l]) {
                 HIP_TRY(hipStreamWaitEvent(st, fork, 0));
+                if (changeover) HIP_TRY(hipStreamWaitEvent(st, hp.ev_path_end, 0));
                 used[l] = true;
             }
             if (prev != L && prev != l) HIP_TRY(hipStreamWaitEvent(st, hp.ev_up[prev], 0));
@@ -846,8 +871,10 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->reduce_serial_loads = 1;
     cfg->reduce_nontemporal = 3;
     cfg->copy_nontemporal = 3;
-    cfg->host_engine = FLEX_ENGINE_HYBRID;
+    cfg->host_engine = FLEX_ENGINE_AUTO;
     cfg->host_blocks = 8;
+    cfg->host_down_blocks = 6;
+    cfg->hybrid_min_bytes = 4u << 20;
     cfg->host_die_shift = 2;
     cfg->min_step_bytes = 256u << 10;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
@@ -877,7 +904,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
+        c.host_blocks > 65536 || c.host_down_blocks < 1 || c.host_down_blocks > 65536 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
         c.host_die_shift > 3 || c.reduce_serial_loads > 2 || c.launch_shape > FLEX_SHAPE_BLOCK ||
         !hints_ok(c.reduce_nontemporal) || !hints_ok(c.copy_nontemporal) || b.share_total == 0 ||
         c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.accept_pairs < 1 ||
@@ -914,7 +941,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     // kernels that read or write pinned memory over PCIe: a fixed, small number
     // of workgroups striding over the step, kept on few dies, so that waves
     // waiting on the link do not crowd the device path off the memory system
-    m->link_reduce_shape = {256, 1, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    m->link_reduce_shape = {256, 1, 0, (uint32_t)cus, c.host_down_blocks, c.host_die_shift};
     m->link_copy_shape = {256, 2, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
     // hybrid engine: kernels that drain a staging buffer run at HBM speed and
     // are over in microseconds; all loads of a tile in flight
@@ -945,16 +972,21 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
         m->naux = (int)c.num_aux_paths;
         for (int a = 0; a < m->naux; ++a) {
             HostPath& hp = m->aux[a];
-            // the first auxiliary path uses the configured engine, the second the next one
-            hp.engine = (int)((c.host_engine + (uint32_t)a) % 3u);
+            // the first auxiliary path uses the configured engine, the second the DMA engines
+            // (or the copy kernels, if the first one has the DMA engines)
+            hp.engine = a == 0 ? (int)c.host_engine
+                               : (c.host_engine == FLEX_ENGINE_SDMA ? FLEX_ENGINE_KERNEL : FLEX_ENGINE_SDMA);
+            const bool events = c.slot_sync == FLEX_SYNC_EVENTS;
+            const bool hybrid = hp.engine == FLEX_ENGINE_HYBRID || (hp.engine == FLEX_ENGINE_AUTO && events);
+            const bool lanes = hybrid && events;
+            const bool pipeline = !(hp.engine == FLEX_ENGINE_HYBRID && events);
             // side streams at the default priority
-            const bool lanes = hp.engine == FLEX_ENGINE_HYBRID && c.slot_sync == FLEX_SYNC_EVENTS;
-            if (!lanes) {
+            if (pipeline) {
                 CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
                 CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
-                if (hp.engine == FLEX_ENGINE_HYBRID)
-                    CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
+                if (hybrid && !lanes) CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
             }
+            CREATE_TRY(hipEventCreateWithFlags(&hp.ev_path_end, hipEventDisableTiming));
             for (uint32_t s = 0; s < c.num_slots; ++s) {
                 if (lanes) {
                     hipStream_t st = nullptr;
@@ -974,7 +1006,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
                     CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
                     vec->push_back(e);
                 }
-                if (hp.engine == FLEX_ENGINE_HYBRID) {
+                if (hybrid) {
                     char* d = nullptr;
                     CREATE_TRY(hipMalloc((void**)&d, slot_bytes));
                     hp.stage.push_back(d);
