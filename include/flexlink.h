@@ -209,21 +209,19 @@ int flex_partition_paths(uint64_t count, const uint32_t* units, int npaths, uint
  * Communicator (paper: Section "Communicator").
  * ---------------------------------------------------------------------- */
 enum flex_host_engine {
-    FLEX_ENGINE_AUTO = 0,   /* default: FLEX_ENGINE_KERNEL for host parts shorter than hybrid_min_bytes per
-                               peer (lowest latency: about 55 us for the first byte against 180 us),
-                               FLEX_ENGINE_HYBRID for longer ones (highest rate, no compute units held while
-                               the data comes back).  With FLEX_SYNC_COUNTERS it is FLEX_ENGINE_KERNEL. */
-    FLEX_ENGINE_HYBRID = 1, /* Producer stage: one small copy kernel writes all peers' pieces into the pinned
-                               slot over PCIe; consumer stage: one hipMemcpyAsync (DMA engine) brings the slot
-                               back into a device staging buffer, and a kernel reduces from there (AllReduce)
-                               or places the pieces (AllGather).  On MI355X a DMA engine writes host memory
-                               at half the rate of a copy kernel, and a kernel that reads host memory
-                               competes with the producer's writes for the same request queues. */
-    FLEX_ENGINE_KERNEL = 2, /* both stages are small HIP kernels that write to / read from the pinned buffer
-                               over PCIe; for AllReduce the second stage is the reduce kernel itself, reading
-                               the peers straight from pinned memory */
-    FLEX_ENGINE_SDMA = 3    /* both stages are hipMemcpyAsync copies (DMA engines), one per peer and step;
-                               AllReduce then reduces once from a device scratch buffer */
+    FLEX_ENGINE_KERNEL = 0, /* default: both stages are small HIP kernels that write to / read from the pinned
+                               buffer over PCIe; for AllReduce the second stage is the reduce kernel itself,
+                               reading the peers straight from pinned memory.  Lowest latency (about 55 us
+                               for the first byte) and, with the workgroup counts below, the steadiest rate
+                               in both directions at once on MI355X */
+    FLEX_ENGINE_HYBRID = 1, /* producer stage: the same copy kernel; consumer stage: one hipMemcpyAsync (DMA
+                               engine) brings the slot back into a device staging buffer, and a kernel reduces
+                               from there (AllReduce) or places the pieces (AllGather).  Holds no compute
+                               units while the data comes back; about 180 us for the first byte, and its
+                               rate varies from box to box and drops when calls are queued back to back */
+    FLEX_ENGINE_SDMA = 2    /* both stages are hipMemcpyAsync copies (DMA engines), one per peer and step;
+                               AllReduce then reduces once from a device scratch buffer.  A DMA engine
+                               writes host memory at half the rate of a copy kernel on MI355X */
 };
 
 enum flex_slot_sync {
@@ -245,8 +243,7 @@ typedef struct flex_config {
     uint32_t struct_size;        /* sizeof(flex_config_t) as the caller's header declares it.
                                     flex_config_default() fills it in; flex_comm_create() refuses any other
                                     value, so a caller built against another layout fails loudly */
-    uint32_t num_slots;          /* transit slots in the ring; 2 = the paper's double buffering; default 3, which
-                                    also hides the hand-off between a DMA copy and the kernel behind it */
+    uint32_t num_slots;          /* transit slots in the ring; 2 (default) = the paper's double buffering */
     uint64_t chunk_bytes;        /* transit buffer bytes per peer and pipeline step (paper: 4 MB; default
                                     4 MiB); one pinned slot holds (nranks-1) * chunk_bytes */
     uint64_t min_split_bytes;    /* messages shorter than this per rank are never split (default 64 KiB) */
@@ -269,7 +266,7 @@ typedef struct flex_config {
                                     3 (default) non-temporal loads and stores.  Plain stores let a reused
                                     output stay in the 256 MB memory-side cache (an nccl-tests style loop) */
     uint32_t copy_nontemporal;   /* same for the copy kernel */
-    uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_AUTO; the
+    uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_KERNEL; the
                                     engine with hipMemcpyAsync in both directions is FLEX_ENGINE_SDMA) */
     uint32_t host_blocks;        /* workgroups (of 256 threads) of the producer-stage copy kernel, which writes
                                     pinned memory (default 8: two already fill the link) */
@@ -284,11 +281,10 @@ typedef struct flex_config {
     uint32_t num_aux_paths;      /* host-staged paths: 1 (default) = FLEX_PATH_HOST with host_engine;
                                     2 = also FLEX_PATH_HOST2 on FLEX_ENGINE_SDMA (on FLEX_ENGINE_KERNEL if the
                                     first one is FLEX_ENGINE_SDMA) */
-    uint32_t host_down_blocks;   /* FLEX_ENGINE_KERNEL: workgroups of the consumer-stage kernel, which reads
+    uint32_t host_down_blocks;   /* FLEX_ENGINE_KERNEL: workgroups of the consumer-stage reduce kernel, which reads
                                     pinned memory (default 6; measured on MI355X next to 8 producer workgroups:
                                     4 give 34.7, 6 give 41.9, 8 give 38.2, 16 give 31 GB/s each way) */
-    uint32_t hybrid_min_bytes;   /* FLEX_ENGINE_AUTO: host parts of at least this many bytes per peer take
-                                    FLEX_ENGINE_HYBRID (default 4 MiB) */
+    uint32_t reserved;
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

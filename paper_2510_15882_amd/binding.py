@@ -21,7 +21,7 @@ FLEX_ALLREDUCE, FLEX_ALLGATHER, FLEX_REDUCESCATTER, FLEX_ALLTOALL = 0, 1, 2, 3
 FLEX_PATH_DEVICE, FLEX_PATH_HOST, FLEX_PATH_HOST2 = 0, 1, 2
 FLEX_SPLIT_STATIC, FLEX_SPLIT_ADAPTIVE = 0, 1
 FLEX_STAGE_TUNING, FLEX_STAGE_RUNTIME = 1, 2
-FLEX_ENGINE_AUTO, FLEX_ENGINE_HYBRID, FLEX_ENGINE_KERNEL, FLEX_ENGINE_SDMA = 0, 1, 2, 3
+FLEX_ENGINE_KERNEL, FLEX_ENGINE_HYBRID, FLEX_ENGINE_SDMA = 0, 1, 2
 FLEX_SHAPE_WAVE, FLEX_SHAPE_BLOCK = 0, 1
 FLEX_SYNC_EVENTS, FLEX_SYNC_COUNTERS = 0, 1
 
@@ -60,7 +60,7 @@ class Config(_Struct):
                 ("tune_accept_check", u32), ("accept_pairs", u32), ("launch_shape", u32),
                 ("reduce_serial_loads", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("host_die_shift", u32), ("min_step_bytes", u32),
-                ("slot_sync", u32), ("num_aux_paths", u32), ("host_down_blocks", u32), ("hybrid_min_bytes", u32),
+                ("slot_sync", u32), ("num_aux_paths", u32), ("host_down_blocks", u32), ("reserved", u32),
                 ("balancer", BalancerCfg)]
 
 

@@ -158,20 +158,13 @@ struct HostPath {
     std::vector<hipStream_t> lane;
     std::vector<hipEvent_t> ev_up, ev_end;
     hipStream_t tail = nullptr;  // stream the last call's final step ended on
-    // FLEX_ENGINE_AUTO uses the lanes for long host parts and the two-stream
-    // pipeline for short ones; both work on the same pinned slots, so a call that
-    // changes over first waits for the end of the call before it
-    hipEvent_t ev_path_end = nullptr;
-    int last_way = 0;            // 0 = nothing yet, 1 = two-stream pipeline, 2 = lanes
-    int call_engine = FLEX_ENGINE_KERNEL;  // engine of the call being enqueued
+
     uint64_t chunk_seq = 0;  // steps staged since creation; slot = seq % num_slots
     char* scratch = nullptr;  // DMA engine, reductions only: one stripe per peer
     size_t scratch_stride = 0;
 
-    bool on_lanes() const { return call_engine == FLEX_ENGINE_HYBRID && !lane.empty(); }
-    hipStream_t last_stream() const {
-        return on_lanes() ? tail : call_engine == FLEX_ENGINE_HYBRID ? s_fin : s_down;
-    }
+    bool lanes() const { return !lane.empty(); }
+    hipStream_t last_stream() const { return lanes() ? tail : engine == FLEX_ENGINE_HYBRID ? s_fin : s_down; }
 
     void quiesce() {
         for (hipStream_t st : {s_up, s_down, s_fin})
@@ -191,7 +184,6 @@ struct HostPath {
         for (hipStream_t st : {s_up, s_down, s_fin})
             if (st) (void)hipStreamDestroy(st);
         for (hipStream_t st : lane) (void)hipStreamDestroy(st);
-        if (ev_path_end) (void)hipEventDestroy(ev_path_end);
         *this = HostPath();
     }
 };
@@ -204,7 +196,8 @@ struct flex_comm {
     size_t max_bytes = 0;
     flex_config_t cfg;
     flex::LaunchShape reduce_shape, copy_shape;            // device path
-    flex::LaunchShape link_reduce_shape, link_copy_shape;  // kernels that touch pinned memory: few workgroups
+    // kernels that touch pinned memory: few workgroups (producer copy, consumer reduce, consumer copy)
+    flex::LaunchShape link_reduce_shape, link_copy_shape, link_down_copy_shape;
     flex::LaunchShape stage_reduce_shape, stage_copy_shape;  // hybrid engine: kernels that drain a staging buffer
 
     int naux = 0;  // auxiliary (host-staged) paths: path index 1 + a
@@ -229,27 +222,12 @@ struct flex_comm {
     // rounded up to 256 bytes), so the hybrid engine brings a whole step back
     // with one DMA copy.
     int host_path(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
-        hp.call_engine = hp.engine;
-        if (hp.engine == FLEX_ENGINE_AUTO)
-            hp.call_engine = (!hp.lane.empty() && bytes >= cfg.hybrid_min_bytes) ? FLEX_ENGINE_HYBRID
-                                                                                 : FLEX_ENGINE_KERNEL;
-        const int way = hp.on_lanes() ? 2 : 1;
-        const bool changeover = hp.last_way != 0 && hp.last_way != way;
-        hp.last_way = way;
-        int st = way == 2 ? host_path_lanes(hp, job, bytes, fork, changeover)
-                          : host_path_pipeline(hp, job, bytes, fork, changeover);
-        if (st) return st;
-        HIP_TRY(hipEventRecord(hp.ev_path_end, hp.last_stream()));
-        return FLEX_OK;
-    }
-
-    int host_path_pipeline(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork, bool changeover) {
+        if (hp.lanes()) return host_path_lanes(hp, job, bytes, fork);
         HIP_TRY(hipStreamWaitEvent(hp.s_up, fork, 0));
-        if (changeover) HIP_TRY(hipStreamWaitEvent(hp.s_up, hp.ev_path_end, 0));
         const size_t nslots = hp.pinned.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
         const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
-        const int engine = hp.call_engine;
+        const int engine = hp.engine;
         const bool counters = cfg.slot_sync == FLEX_SYNC_COUNTERS;
 
         size_t off = 0;
@@ -335,7 +313,7 @@ struct flex_comm {
                     dn_src[j] = up_dst[j];
                     dn_dst[j] = job.peer_dst[j] + off;
                 }
-                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, link_copy_shape, hp.s_down));
+                LAUNCH_TRY(flex::launch_gather_copy(dn_src, dn_dst, nn, job.npeers, link_down_copy_shape, hp.s_down));
             } else {
                 for (int j = 0; j < job.npeers; ++j)
                     HIP_TRY(hipMemcpyAsync(job.peer_dst[j] + off, up_dst[j], n, hipMemcpyHostToDevice, hp.s_down));
@@ -371,7 +349,7 @@ struct flex_comm {
     // another on the upstream direction of the link while the DMA copies of
     // earlier steps occupy the downstream one; with three lanes the hand-off
     // between a DMA copy and the kernel behind it is hidden as well.
-    int host_path_lanes(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork, bool changeover) {
+    int host_path_lanes(HostPath& hp, const HostJob& job, size_t bytes, hipEvent_t fork) {
         const size_t L = hp.lane.size();
         const size_t es = job.reduce ? flex::dtype_size(job.dtype) : 1;
         const std::vector<uint64_t> steps = flex::plan_steps(bytes, cfg.chunk_bytes, cfg.min_step_bytes);
@@ -390,7 +368,6 @@ struct flex_comm {
             char* stage = hp.stage[l];
             if (!used[l]) {
                 HIP_TRY(hipStreamWaitEvent(st, fork, 0));
-                if (changeover) HIP_TRY(hipStreamWaitEvent(st, hp.ev_path_end, 0));
                 used[l] = true;
             }
             if (prev != L && prev != l) HIP_TRY(hipStreamWaitEvent(st, hp.ev_up[prev], 0));
@@ -852,7 +829,7 @@ int flex_config_default(flex_config_t* cfg) {
     memset(cfg, 0, sizeof *cfg);
     cfg->struct_size = (uint32_t)sizeof *cfg;
     cfg->chunk_bytes = 4u << 20;
-    cfg->num_slots = 3;
+    cfg->num_slots = 2;
     cfg->max_host_units = 2500;
     cfg->split_align_elems = 2048;
     cfg->min_split_bytes = 64u << 10;
@@ -871,10 +848,9 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->reduce_serial_loads = 1;
     cfg->reduce_nontemporal = 3;
     cfg->copy_nontemporal = 3;
-    cfg->host_engine = FLEX_ENGINE_AUTO;
+    cfg->host_engine = FLEX_ENGINE_KERNEL;
     cfg->host_blocks = 8;
     cfg->host_down_blocks = 6;
-    cfg->hybrid_min_bytes = 4u << 20;
     cfg->host_die_shift = 2;
     cfg->min_step_bytes = 256u << 10;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
@@ -943,6 +919,9 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     // waiting on the link do not crowd the device path off the memory system
     m->link_reduce_shape = {256, 1, 0, (uint32_t)cus, c.host_down_blocks, c.host_die_shift};
     m->link_copy_shape = {256, 2, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
+    // reading pinned memory is latency-bound: four vectors in flight per lane (about 110 KiB in all
+    // with one workgroup per peer) bring 35 GB/s back where two bring 29
+    m->link_down_copy_shape = {256, 4, 0, (uint32_t)cus, c.host_blocks, c.host_die_shift};
     // hybrid engine: kernels that drain a staging buffer run at HBM speed and
     // are over in microseconds; all loads of a tile in flight
     m->stage_reduce_shape = {256, 1, 0, (uint32_t)cus, 0};
@@ -976,17 +955,14 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
             // (or the copy kernels, if the first one has the DMA engines)
             hp.engine = a == 0 ? (int)c.host_engine
                                : (c.host_engine == FLEX_ENGINE_SDMA ? FLEX_ENGINE_KERNEL : FLEX_ENGINE_SDMA);
-            const bool events = c.slot_sync == FLEX_SYNC_EVENTS;
-            const bool hybrid = hp.engine == FLEX_ENGINE_HYBRID || (hp.engine == FLEX_ENGINE_AUTO && events);
-            const bool lanes = hybrid && events;
-            const bool pipeline = !(hp.engine == FLEX_ENGINE_HYBRID && events);
+            const bool hybrid = hp.engine == FLEX_ENGINE_HYBRID;
+            const bool lanes = hybrid && c.slot_sync == FLEX_SYNC_EVENTS;
             // side streams at the default priority
-            if (pipeline) {
+            if (!lanes) {
                 CREATE_TRY(hipStreamCreateWithFlags(&hp.s_up, hipStreamNonBlocking));
                 CREATE_TRY(hipStreamCreateWithFlags(&hp.s_down, hipStreamNonBlocking));
-                if (hybrid && !lanes) CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
+                if (hybrid) CREATE_TRY(hipStreamCreateWithFlags(&hp.s_fin, hipStreamNonBlocking));
             }
-            CREATE_TRY(hipEventCreateWithFlags(&hp.ev_path_end, hipEventDisableTiming));
             for (uint32_t s = 0; s < c.num_slots; ++s) {
                 if (lanes) {
                     hipStream_t st = nullptr;

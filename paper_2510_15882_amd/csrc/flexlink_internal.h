@@ -119,7 +119,7 @@ inline std::vector<uint64_t> plan_steps(uint64_t bytes, uint64_t chunk, uint64_t
 
 struct LaunchShape {
     uint32_t threads;       // workgroup size: 64 (one tile of 1 KiB per workgroup) or 256
-    uint32_t unroll;        // copy kernel: 16-byte vectors in flight per thread (1 or 2)
+    uint32_t unroll;        // copy kernel: 16-byte vectors in flight per thread (1, 2, 4 or 6)
     uint32_t nontemporal;   // bit 0: loads, bit 1: stores
     uint32_t num_cus;       // compute units of the device
     uint32_t max_blocks;    // 0 = one workgroup per tile; else the grid is this many workgroups striding over the tiles

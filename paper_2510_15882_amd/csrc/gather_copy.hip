@@ -123,7 +123,7 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     if (longest == 0) return 0;
 
     const uint32_t threads = shape.threads;
-    const uint32_t unroll = shape.unroll == 2 ? 2 : 1;
+    const uint32_t unroll = shape.unroll == 2 || shape.unroll == 4 || shape.unroll == 6 ? shape.unroll : 1;
     const uint64_t tile_bytes = (uint64_t)threads * unroll * 16;
     uint64_t gx = (longest + tile_bytes - 1) / tile_bytes;
     if (shape.max_blocks) {
@@ -137,8 +137,12 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     gx <<= a.shift;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;
-    return unroll == 2 ? launch_one<2>(a, grid, threads, shape.nontemporal, s)
-                       : launch_one<1>(a, grid, threads, shape.nontemporal, s);
+    switch (unroll) {
+        case 2: return launch_one<2>(a, grid, threads, shape.nontemporal, s);
+        case 4: return launch_one<4>(a, grid, threads, shape.nontemporal, s);
+        case 6: return launch_one<6>(a, grid, threads, shape.nontemporal, s);
+        default: return launch_one<1>(a, grid, threads, shape.nontemporal, s);
+    }
 }
 
 }  // namespace flex

@@ -302,7 +302,7 @@ def test_every_launch_shape_gives_the_same_bits(shape, nt):
 
 # ---------------------------------------------------------- ReduceScatter
 
-@pytest.mark.parametrize("engine", [0, 1, 2, 3])
+@pytest.mark.parametrize("engine", [0, 1, 2])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_reducescatter_is_the_rank_slice_and_composes_to_allreduce(dtype, engine):
     n = 8
@@ -343,8 +343,8 @@ def test_alltoall_receive_buffer(dtype):
     for cnt in (0, 1, 2049, 40001, (1 << 17) + 2048):
         bufs = [wl.random_bits(n * cnt, dtype, 60 + r, DEV) for r in range(n)]
         host = [wl.to_numpy_bits(b) for b in bufs]
-        for rank, units, engine, paths in ((0, 0, 0, 1), (3, 1500, 0, 1), (7, 1500, 1, 1), (2, 1500, 2, 1), (4, 1500, 3, 1),
-                                           (5, 700, 0, 2), (6, 700, 3, 2)):
+        for rank, units, engine, paths in ((0, 0, 0, 1), (3, 1500, 0, 1), (7, 1500, 1, 1), (2, 1500, 2, 1), (5, 700, 0, 2),
+                                           (6, 700, 1, 2), (4, 700, 2, 2)):
             with Comm(rank=rank, max_host_units=10000, host_engine=engine, num_aux_paths=paths,
                       min_step_bytes=16 << 10) as comm:
                 fx.flex_set_split_paths(comm, fx.FLEX_ALLTOALL, fx.FLEX_SPLIT_STATIC, (units,) * paths)
@@ -378,7 +378,6 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
             cfg.chunk_bytes, cfg.host_die_shift, cfg.num_aux_paths = chunk, shift, paths
             cfg.reduce_serial_loads = (engine + sync + shift) % 3
             cfg.min_step_bytes, cfg.min_split_bytes = 8 << 10, 4 << 10
-            cfg.hybrid_min_bytes = 24 << 10            # the automatic engine changes over inside the size range drawn
             comms[key] = fx.flex_comm_create(nranks, rank, 16 << 20, cfg)
         return comms[key]
 
@@ -396,7 +395,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
             lead0 = rng.randrange(0, 16 // es)
             leads = [lead0 if same_lead else rng.randrange(0, 16 // es) for _ in range(nranks)]
             out_lead = lead0 if rng.random() < 0.7 else rng.randrange(0, 16 // es)
-            engine, sync = rng.randrange(4), rng.randrange(2)
+            engine, sync = rng.randrange(3), rng.randrange(2)
             chunk = rng.choice([16 << 10, 64 << 10, 1 << 20])
             shift, paths = rng.randrange(4), rng.choice([1, 1, 2])
             units = rng.choice([0, 1, 37, 500, 2500, 6000, 10000])
@@ -446,7 +445,7 @@ def test_random_calls_of_all_four_collectives_match_the_oracle():
 
 # ------------------------------------------------- split over both paths
 
-ENGINES = [fx.FLEX_ENGINE_AUTO, fx.FLEX_ENGINE_HYBRID, fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_SDMA]
+ENGINES = [fx.FLEX_ENGINE_KERNEL, fx.FLEX_ENGINE_HYBRID, fx.FLEX_ENGINE_SDMA]
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -577,36 +576,6 @@ def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
         st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
         assert st.calls == 50 and st.split_calls == 50 and st.samples == 50 and st.blocking_reads == 0
         assert st.last_time_s[0] > 0 and st.last_time_s[1] > 0
-
-
-def test_automatic_engine_changes_over_between_queued_calls():
-    # FLEX_ENGINE_AUTO: short host parts go through the two-stream kernel pipeline,
-    # long ones through the DMA lanes, on the same pinned slots; calls of both
-    # kinds are queued back to back without host synchronisation, on one stream
-    # and on two streams in turn
-    count = (1 << 21) + 2048 + 7
-    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
-    want = oracle_allreduce(bufs)
-    want_ag = oracle_allgather(bufs)
-    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    with Comm(max_host_units=10000, hybrid_min_bytes=256 << 10, chunk_bytes=128 << 10, min_step_bytes=16 << 10) as comm:
-        for two_streams in (False, True):
-            plan = [1, 5000, 30, 2200, 10000, 1, 1, 9000, 300, 300, 4000, 2]      # 4 KiB ... 4 MiB per peer
-            outs = [torch.zeros(count, dtype=torch.bfloat16, device=DEV) for _ in plan]
-            outs_ag = [torch.zeros(8 * count, dtype=torch.bfloat16, device=DEV) for _ in plan[:4]]
-            torch.cuda.synchronize()
-            for k, units in enumerate(plan):
-                st = streams[k % 2 if two_streams else 0]
-                fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
-                fx.flex_allreduce_local(comm, bufs, outs[k], stream=st)
-                if k < 4:
-                    fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
-                    fx.flex_allgather_local(comm, bufs, outs_ag[k], stream=st)
-            torch.cuda.synchronize()
-            for k, o in enumerate(outs):
-                assert_same_bits(o, want, "call %d, %d units, two streams %s" % (k, plan[k], two_streams))
-            for k, o in enumerate(outs_ag):
-                assert np.array_equal(wl.to_numpy_bits(o), want_ag), (k, two_streams)
 
 
 # ------------------------------------------------------------ three paths

@@ -33,11 +33,10 @@ def test_struct_layout_defaults_come_through():
     c = fx.flex_config_default()
     import ctypes
     assert c.struct_size == ctypes.sizeof(fx.Config)
-    assert c.chunk_bytes == 4 << 20 and c.num_slots == 3 and c.max_host_units == 2500
+    assert c.chunk_bytes == 4 << 20 and c.num_slots == 2 and c.max_host_units == 2500
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
-    assert (c.host_engine, c.host_blocks, c.host_down_blocks, c.min_step_bytes) == (fx.FLEX_ENGINE_AUTO, 8, 6, 256 << 10)
-    assert c.hybrid_min_bytes == 4 << 20
+    assert (c.host_engine, c.host_blocks, c.host_down_blocks, c.min_step_bytes) == (fx.FLEX_ENGINE_KERNEL, 8, 6, 256 << 10)
     assert c.tune_accept_check == 1 and c.accept_pairs == 3 and c.launch_shape == fx.FLEX_SHAPE_WAVE
     assert c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
     b = c.balancer
