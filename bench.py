@@ -173,6 +173,9 @@ def main():
                     help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
     ap.add_argument("--host-engine", type=int, default=-1, help="0 hybrid, 1 copy kernels, 2 DMA engines")
     ap.add_argument("--host-blocks", type=int, default=0)
+    ap.add_argument("--max-host-units", type=int, default=0,
+                    help="largest host share the communicator accepts (default 2500; 10000 to time the host path alone "
+                         "with --mode static:10000)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is the single-GPU local share; it runs on exactly one GPU "
@@ -216,6 +219,8 @@ def main():
     cfg = fx.flex_config_default()
     if args.host_blocks:
         cfg.host_blocks = args.host_blocks
+    if args.max_host_units:
+        cfg.max_host_units = args.max_host_units
     for key, val in (("reduce_nontemporal", args.reduce_nt), ("copy_nontemporal", args.copy_nt),
                      ("host_engine", args.host_engine), ("reduce_serial_loads", args.reduce_serial),
                      ("launch_shape", args.launch_shape)):
@@ -330,7 +335,16 @@ def main():
                % ("" if every == 1 else "%d-th " % every, len(ar_ms)))
         nlaunch = len(ar_ms)
     bytes_per_elem = (N + 1) * 2
-    achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9
+    achieved = bytes_per_elem * dev_elems / (kern_ms * 1e-3) / 1e9 if dev_elems > 0 and kern_ms > 0 else 0.0
+    host_timed = None
+    if split_samples > 0:
+        # the host path of the timed AllReduce calls: fork -> host path done, 7 peers' parts each way
+        host_s = (s_ar1.mean_time_s[1] * s_ar1.samples - s_ar0.mean_time_s[1] * s_ar0.samples) / split_samples
+        host_elems = s_ar1.last_count - s_ar1.last_split
+        pcie = (N - 1) * host_elems * 2 / host_s / 1e9 if host_s > 0 else 0.0
+        host_timed = {"allreduce_host_share_pct": 100.0 * host_elems / s_ar1.last_count, "host_path_ms": host_s * 1e3,
+                      "pcie_GBs_per_direction": pcie, "pcie_frac_of_64GBs": pcie / PCIE_PEAK_GBS,
+                      "split_calls": int(split_samples)}
     traffic, traffic_note = traffic_from_profiles()
     roofline = {"bound": "hbm", "kernel": "reduce_n_kernel<8, bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -366,6 +380,8 @@ def main():
     }
     if tune:
         result["tune"] = tune
+    if host_timed:
+        result["host_path_timed"] = host_timed
 
     # ---- untimed extras ------------------------------------------------------
     if not args.no_extras:
