@@ -15,9 +15,3 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C-ABI on cuda:0)")
-
-
-def pytest_collection_modifyitems(config, items):
-    # GPU tests are selected with -m gpu; when they are selected on a machine
-    # without a GPU they fail loudly instead of being skipped.
-    pass

@@ -210,6 +210,39 @@ def test_allreduce_raw_bit_patterns_and_specials(dtype, serial):
         assert_same_bits(out[:1000], oracle_allreduce([neg0] * 8), "-0")
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_allreduce_of_two_ranks_on_every_pair_of_bit_patterns(dtype):
+    # N = 2 and all 2^32 ordered pairs (a, b) of 16-bit patterns: every accumulator a
+    # single binary32 add of two widened inputs can produce goes through the kernel's
+    # widening, add and narrowing (for binary16 the hardware converters) and through
+    # the oracle's integer routines; the bits must agree wherever the sum is not a NaN.
+    # Random patterns cannot cover this: the ties and the subnormal / overflow edges
+    # of the narrowing are measure-zero sets.
+    slab_bits = 27                                   # 2^27 pairs per slab, 32 slabs
+    n = 1 << slab_bits
+    a_per_slab = n >> 16
+    idx = torch.arange(n, dtype=torch.int32, device=DEV)
+    b_dev = (idx & 0xFFFF).to(torch.int16).view(dtype)           # b runs through all patterns, fastest
+    hi_dev = (idx >> 16).to(torch.int32)
+    del idx
+    idx_np = np.arange(n, dtype=np.uint32)
+    b_np = (idx_np & 0xFFFF).astype(np.uint16)
+    hi_np = (idx_np >> 16).astype(np.uint16)
+    del idx_np
+    view = (lambda x: x) if dtype == torch.bfloat16 else (lambda x: x.view(np.float16))
+    out = torch.empty(n, dtype=dtype, device=DEV)
+    with Comm(nranks=2, max_bytes=2 * n) as comm:
+        for slab in range(1 << (32 - slab_bits)):
+            base = slab * a_per_slab
+            a_dev = (hi_dev + base).to(torch.int16).view(dtype)
+            fx.flex_allreduce_local(comm, [a_dev, b_dev], out)
+            want = oc.allreduce([view(hi_np + np.uint16(base)), view(b_np)])
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, "a = 0x%04x.., all b" % base)
+            if slab % 8 == 0:
+                say("pairs", dtype, "slab", slab, "ok")
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_allreduce_misaligned_pointers_and_in_place(dtype):
     count = 100003

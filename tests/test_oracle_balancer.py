@@ -171,6 +171,29 @@ def test_alg1_invariants_under_arbitrary_timings(seed, npaths):
     assert all(S[p] == 0 for p in range(1, npaths) if p not in active)
 
 
+def test_share_ceiling_trims_a_transfer_and_an_empty_transfer_counts_as_calm():
+    # hand-executed: three paths, primary slowest every round, path 2 fastest, ceiling 8 on both
+    # auxiliaries, step 4, two calm rounds end the tuning.
+    # r1: 0 -> 2 wants 4, room 8-5 = 3: S = [87, 5, 8]          calm 0
+    # r2: 0 -> 2 wants 4, room 0: nothing moves                  calm 1
+    # r3: the same                                               calm 2 -> stop
+    trace = []
+    S, live = ob.initial_tune([90, 5, 5], lambda S, A: [3.0, 2.0, 1.0], step0=4, stability_required=2,
+                              cap=[None, 8, 8], trace=trace)
+    assert [t["S"] for t in trace] == [[87, 5, 8], [87, 5, 8], [87, 5, 8]]
+    assert [t["stability_count"] for t in trace] == [0, 1, 2] and S == [87, 5, 8] and live == {0, 1, 2}
+    # without the ceiling the same timings keep draining the primary path
+    S, live = ob.initial_tune([90, 5, 5], lambda S, A: [3.0, 2.0, 1.0], step0=4, stability_required=2, max_iters=5)
+    assert S == [70, 5, 25]
+    # the primary path has no ceiling: a slow auxiliary still hands everything back
+    S, live = ob.initial_tune([90, 5, 5], lambda S, A: [1.0, 9.0, 2.0], step0=4, cap=[None, 8, 8], max_iters=2)
+    assert S == [95, 0, 5] and live == {0, 2}
+    # Stage 2: a trimmed move is a move, an empty one is not
+    r = ob.RuntimeAdjuster([9900, 98, 2], {0, 1, 2}, window=1, threshold=0.10, step=4, cap=[None, 100, 100])
+    assert r.observe([3.0, 1.0, 2.0]) and r.S == [9898, 100, 2] and r.adjustments == 1
+    assert not r.observe([3.0, 1.0, 2.0]) and r.S == [9898, 100, 2] and r.adjustments == 1
+
+
 # ----------------------------------------------------- InitializeShares
 
 def test_initialize_shares_is_bandwidth_proportional():
