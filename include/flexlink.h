@@ -284,7 +284,10 @@ typedef struct flex_config {
     uint32_t host_down_blocks;   /* FLEX_ENGINE_KERNEL: workgroups of the consumer-stage reduce kernel, which reads
                                     pinned memory (default 6; measured on MI355X next to 8 producer workgroups:
                                     4 give 34.7, 6 give 41.9, 8 give 38.2, 16 give 31 GB/s each way) */
-    uint32_t reserved;
+    uint32_t sample_every;       /* the Evaluator times every sample_every-th split call (default 1: every call, the
+                                    window holds consecutive calls as in the paper); the other split calls fork and
+                                    join with ordering-only events, which saves about 6 us of the 15 us a split call
+                                    costs on top of its kernels.  flex_comm_tune always times every call */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
 

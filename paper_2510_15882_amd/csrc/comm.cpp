@@ -206,6 +206,11 @@ struct flex_comm {
 
     Ring ring;
     HipEventApi events;
+    // split calls the Evaluator does not sample are forked and joined with
+    // ordering-only events (a timing event costs about 2 us of stream time)
+    hipEvent_t fork_untimed = nullptr;
+    hipEvent_t join_untimed[kMaxAux] = {nullptr, nullptr, nullptr};
+    uint64_t split_seq = 0;  // split calls issued so far, all collectives
     hipEvent_t t0 = nullptr, t1 = nullptr;  // whole-call timing in flex_comm_tune
 
     CollState coll[4];  // indexed by flex_coll
@@ -529,6 +534,11 @@ struct flex_comm {
             return flex::fail(FLEX_ERR_STATE,
                               "a call that uses a host path cannot be captured into a graph: set the host "
                               "share to 0 for captured calls");
+        *rec_out = nullptr;
+        if (split_seq++ % cfg.sample_every != 0) {  // not sampled: no record, no timing events
+            ++coll[c].split_calls;
+            return FLEX_OK;
+        }
         TimingRecord* rec;
         int st = ring.acquire(events, [this](const TimingRecord& r, const double* T) { consume(r, T); }, &rec);
         if (st) return st;
@@ -545,8 +555,8 @@ struct flex_comm {
     // nothing, so the record goes back; whatever the call did enqueue on the
     // side streams is waited for, so that nothing of it still runs on the
     // caller's buffers when the error is returned.
-    int abandon_split_call(int c, int status) {
-        ring.abandon();
+    int abandon_split_call(int c, bool sampled, int status) {
+        if (sampled) ring.abandon();
         --coll[c].split_calls;
         for (int a = 0; a < naux; ++a) aux[a].quiesce();
         return status;
@@ -649,21 +659,22 @@ int flex_comm::reduce(int c, const char* who, const void* const* bufs, void* out
     st = begin_split_call(c, count * es, adaptive, generation, stream, &rec);
     if (st) return st;
     st = split_reduce(rec, start, bufs, out, dtype, stream);
-    return st ? abandon_split_call(c, st) : FLEX_OK;
+    return st ? abandon_split_call(c, rec != nullptr, st) : FLEX_OK;
 }
 
 int flex_comm::split_reduce(TimingRecord* rec, const uint64_t* start, const void* const* bufs, void* out,
                             int dtype, hipStream_t stream) {
     const size_t es = flex::dtype_size(dtype);
-    // fork
-    HIP_TRY(hipEventRecord(rec->fork, stream));
+    // fork (rec == nullptr: the Evaluator does not sample this call)
+    hipEvent_t fork = rec ? rec->fork : fork_untimed;
+    HIP_TRY(hipEventRecord(fork, stream));
 
     // device path: head of the message, straight from HBM
     if (start[1] > 0) {
         LAUNCH_TRY(flex::launch_reduce_n(bufs, nranks, out, start[1], dtype, reduce_shape, stream));
-        rec->used_mask |= 1u;
+        if (rec) rec->used_mask |= 1u;
     }
-    HIP_TRY(hipEventRecord(rec->done[0], stream));
+    if (rec) HIP_TRY(hipEventRecord(rec->done[0], stream));
 
     // host paths: every peer's part goes device -> pinned slot -> device and is
     // reduced in the same rank order; the local contribution never leaves HBM
@@ -684,11 +695,12 @@ int flex_comm::split_reduce(TimingRecord* rec, const uint64_t* start, const void
             job.peer_dst[job.npeers] = hp.scratch ? hp.scratch + (size_t)job.npeers * hp.scratch_stride : nullptr;
             ++job.npeers;
         }
-        int st = host_path(hp, job, (hi - lo) * es, rec->fork);
+        int st = host_path(hp, job, (hi - lo) * es, fork);
         if (st) return st;
-        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
-        rec->used_mask |= 1u << (a + 1);
-        HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));  // join
+        hipEvent_t done = rec ? rec->done[a + 1] : join_untimed[a];
+        HIP_TRY(hipEventRecord(done, hp.last_stream()));
+        if (rec) rec->used_mask |= 1u << (a + 1);
+        HIP_TRY(hipStreamWaitEvent(stream, done, 0));  // join
     }
     return FLEX_OK;
 }
@@ -745,16 +757,19 @@ int flex_comm::gather(int c, const char* who, const void* const* slices, void* o
     st = begin_split_call(c, slice_bytes, adaptive, generation, stream, &rec);
     if (st) return st;
     st = split_gather(rec, start, src, dst, bytes, slices, es, stream);
-    return st ? abandon_split_call(c, st) : FLEX_OK;
+    return st ? abandon_split_call(c, rec != nullptr, st) : FLEX_OK;
 }
 
 int flex_comm::split_gather(TimingRecord* rec, const uint64_t* start, const void* const* src, void* const* dst,
                             const uint64_t* bytes, const void* const* slices, size_t es, hipStream_t stream) {
-    HIP_TRY(hipEventRecord(rec->fork, stream));
+    hipEvent_t fork = rec ? rec->fork : fork_untimed;
+    HIP_TRY(hipEventRecord(fork, stream));
 
     LAUNCH_TRY(flex::launch_gather_copy(src, dst, bytes, nranks, copy_shape, stream));
-    rec->used_mask |= 1u;
-    HIP_TRY(hipEventRecord(rec->done[0], stream));
+    if (rec) {
+        rec->used_mask |= 1u;
+        HIP_TRY(hipEventRecord(rec->done[0], stream));
+    }
 
     for (int a = 0; a < naux; ++a) {
         const uint64_t lo = start[a + 1], hi = start[a + 2];
@@ -767,11 +782,12 @@ int flex_comm::split_gather(TimingRecord* rec, const uint64_t* start, const void
             job.peer_dst[job.npeers] = (char*)dst[r] + lo * es;
             ++job.npeers;
         }
-        int st = host_path(hp, job, (hi - lo) * es, rec->fork);
+        int st = host_path(hp, job, (hi - lo) * es, fork);
         if (st) return st;
-        HIP_TRY(hipEventRecord(rec->done[a + 1], hp.last_stream()));
-        rec->used_mask |= 1u << (a + 1);
-        HIP_TRY(hipStreamWaitEvent(stream, rec->done[a + 1], 0));
+        hipEvent_t done = rec ? rec->done[a + 1] : join_untimed[a];
+        HIP_TRY(hipEventRecord(done, hp.last_stream()));
+        if (rec) rec->used_mask |= 1u << (a + 1);
+        HIP_TRY(hipStreamWaitEvent(stream, done, 0));
     }
     return FLEX_OK;
 }
@@ -786,6 +802,7 @@ int flex_comm::measure_split(int c, const void* const* bufs, void* out, size_t c
     for (int p = 1; p < FLEX_MAX_PATHS; ++p) cs.static_units[p] = p < npaths() ? units[p] : 0;
     std::vector<double> t[FLEX_MAX_PATHS];
     for (uint32_t k = 0; k < cfg.tune_reps + 1; ++k) {
+        split_seq = 0;  // MeasurePathTimings samples every call
         const uint64_t before = cs.samples;
         int st = collective(c, bufs, out, count, dtype, stream);
         if (st) return st;
@@ -851,6 +868,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->host_engine = FLEX_ENGINE_KERNEL;
     cfg->host_blocks = 8;
     cfg->host_down_blocks = 6;
+    cfg->sample_every = 1;
     cfg->host_die_shift = 2;
     cfg->min_step_bytes = 256u << 10;
     cfg->slot_sync = FLEX_SYNC_EVENTS;
@@ -880,7 +898,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     const flex_balancer_cfg_t& b = c.balancer;
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
-        c.host_blocks > 65536 || c.host_down_blocks < 1 || c.host_down_blocks > 65536 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
+        c.host_blocks > 65536 || c.host_down_blocks < 1 || c.host_down_blocks > 65536 || c.sample_every < 1 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
         c.host_die_shift > 3 || c.reduce_serial_loads > 2 || c.launch_shape > FLEX_SHAPE_BLOCK ||
         !hints_ok(c.reduce_nontemporal) || !hints_ok(c.copy_nontemporal) || b.share_total == 0 ||
         c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.accept_pairs < 1 ||
@@ -928,6 +946,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     m->stage_copy_shape = {256, 2, 0, (uint32_t)cus, 0};
     CREATE_TRY(hipEventCreate(&m->t0));
     CREATE_TRY(hipEventCreate(&m->t1));
+    CREATE_TRY(hipEventCreateWithFlags(&m->fork_untimed, hipEventDisableTiming));
+    for (auto& e : m->join_untimed) CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
 
     if (nranks > 1) {
         if (c.slot_sync == FLEX_SYNC_COUNTERS) {
@@ -1030,6 +1050,9 @@ int flex_comm_destroy(flex_comm_t* m) {
     }
     if (m->t0) (void)hipEventDestroy(m->t0);
     if (m->t1) (void)hipEventDestroy(m->t1);
+    if (m->fork_untimed) (void)hipEventDestroy(m->fork_untimed);
+    for (auto e : m->join_untimed)
+        if (e) (void)hipEventDestroy(e);
     delete m;
     return FLEX_OK;
 }

@@ -611,6 +611,50 @@ def test_back_to_back_calls_on_one_stream_and_repeatability(engine):
         assert st.last_time_s[0] > 0 and st.last_time_s[1] > 0
 
 
+def test_unsampled_split_calls_use_ordering_only_events_and_give_the_same_bits():
+    # sample_every = 4: three of four split calls record no timing events and take no
+    # Evaluator record; results and Stage 2 are unaffected apart from the sampling rate
+    count = (1 << 20) + 2048 + 9
+    bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
+    want = oracle_allreduce(bufs)
+    want_ag = oracle_allgather(bufs)
+    cfg = fx.flex_config_default()
+    with Comm(sample_every=4, chunk_bytes=128 << 10, min_step_bytes=16 << 10, num_aux_paths=2,
+              max_host_units=5000) as comm:
+        fx.flex_set_split_paths(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, (900, 300))
+        fx.flex_set_split_paths(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, (700, 0))
+        outs = [torch.zeros(count, dtype=torch.bfloat16, device=DEV) for _ in range(20)]
+        outs_ag = [torch.zeros(8 * count, dtype=torch.bfloat16, device=DEV) for _ in range(4)]
+        for k, o in enumerate(outs):
+            fx.flex_allreduce_local(comm, bufs, o)
+            if k % 5 == 0:
+                fx.flex_allgather_local(comm, bufs, outs_ag[k // 5])
+        torch.cuda.synchronize()
+        for k, o in enumerate(outs):
+            assert_same_bits(o, want, "call %d" % k)
+        for o in outs_ag:
+            assert np.array_equal(wl.to_numpy_bits(o), want_ag)
+        fx.flex_evaluator_drain(comm)
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+        sg = fx.flex_get_stats(comm, fx.FLEX_ALLGATHER, count, torch.bfloat16)
+        assert st.split_calls == 20 and sg.split_calls == 4
+        assert st.samples + sg.samples == 24 // 4          # every fourth split call of the communicator
+        assert st.last_time_s[0] > 0 and st.last_time_s[1] > 0 and st.last_time_s[2] > 0
+        # Stage 2 still runs, on every fourth call
+        fx.flex_comm_set_shares(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16, [9000, 1000, 0])
+        fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_ADAPTIVE)
+        out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
+        for k in range(4 * cfg.balancer.window):
+            fx.flex_allreduce_local(comm, bufs, out)
+            torch.cuda.synchronize()
+            fx.flex_evaluator_drain(comm)
+        st = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, torch.bfloat16)
+        assert st.balancer.adjustments == 1 and list(st.balancer.shares)[:2] == [9004, 996]
+        assert_same_bits(out, want, "adaptive, sampled every fourth call")
+    with pytest.raises(fx.FlexError):
+        Comm(sample_every=0).__enter__()
+
+
 # ------------------------------------------------------------ three paths
 
 def test_device_path_calls_replay_from_a_graph_and_split_calls_refuse_capture():
