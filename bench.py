@@ -18,9 +18,12 @@ nccl-tests style loops measure) are reported under extras.warm_same_buffers*.
 Prints ONE JSON line.  `value` is algorithmic HBM bytes per second over the
 timed steps (AllReduce (N+1)*S, AllGather 2*N*slice); `roofline` prices the
 dominant kernel (the N-way reduce) against the 8 TB/s HBM3E peak from per-launch
-HIP-event timings taken inside the timed region (every step when --steps <= 50,
-else every 4th: each event is a packet of its own on the stream and three per
-step cost 2 % of the step); `host_path` gives configuration 2's static 5 / 12 /
+HIP-event timings taken inside the timed region (two events around the
+AllReduce call of every 4th step, sample count and p10 / p90 reported: each
+event is a packet of its own on the stream and costs about 2 us of stream time,
+so bracketing every call of every step would cost 2 % of `value`; the AllGather
+call is timed in an untimed leg right after, call by call and in batches of ten
+that share one pair of events); `host_path` gives configuration 2's static 5 / 12 /
 22 % splits with the PCIe rate per direction against 64 GB/s; `extras.ceilings`
 is what plain probe kernels reach on this very box (bench_ceilings.hip);
 `cpu_baseline` is the CPU oracle timed on this machine's host cores.
@@ -164,8 +167,8 @@ def main():
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed warm / static-split / ceilings legs")
     ap.add_argument("--event-every", type=int, default=0,
-                    help="bracket the two calls of every K-th timed step with HIP events (per-kernel times for the "
-                         "roofline); 0 = every step up to 50 steps, every 4th beyond")
+                    help="bracket the AllReduce call of every K-th timed step with HIP events (per-launch times for the "
+                         "roofline); 0 = every 4th step")
     ap.add_argument("--launch-shape", type=int, default=-1, help="0: 64-thread workgroups, 1: 256-thread workgroups")
     ap.add_argument("--reduce-nt", type=int, default=-1)
     ap.add_argument("--copy-nt", type=int, default=-1)
@@ -290,8 +293,8 @@ def main():
     s_ar0 = stats(fx.FLEX_ALLREDUCE, w_ar)
 
     # ---- timed region: exactly --steps steps --------------------------------
-    every = args.event_every if args.event_every > 0 else (1 if args.steps <= 50 else 4)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(0, args.steps, every)]
+    every = args.event_every if args.event_every > 0 else 4
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(0, args.steps, every)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     with torch.cuda.stream(stream):
@@ -301,11 +304,9 @@ def main():
                 e[0].record(stream)
                 ar(k)
                 e[1].record(stream)
-                ag(k)
-                e[2].record(stream)
             else:
                 ar(k)
-                ag(k)
+            ag(k)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     fx.flex_evaluator_drain(comm)
@@ -315,7 +316,27 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = (ar_bytes + ag_bytes) / (ms_per_step * 1e-3) / 1e9
     ar_ms = [e[0].elapsed_time(e[1]) for e in ev]
-    ag_ms = [e[1].elapsed_time(e[2]) for e in ev]
+    # untimed: the AllGather call by call, in the same AR -> AG sequence over the same rotating buffers
+    ev_ag = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(40)]
+    with torch.cuda.stream(stream):
+        for k, e in enumerate(ev_ag):
+            ar(k)
+            e[0].record(stream)
+            ag(k)
+            e[1].record(stream)
+    torch.cuda.synchronize()
+    fx.flex_evaluator_drain(comm)
+    ag_ms = [e[0].elapsed_time(e[1]) for e in ev_ag]
+    # ... and in batches of ten calls between one pair of events (the events' own stream time amortised)
+    ev_batch = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(6)]
+    with torch.cuda.stream(stream):
+        for b, e in enumerate(ev_batch):
+            e[0].record(stream)
+            for k in range(10):
+                ag(10 * b + k)
+            e[1].record(stream)
+    torch.cuda.synchronize()
+    ag_batch_ms = median([e[0].elapsed_time(e[1]) / 10 for e in ev_batch])
 
     # Dominant kernel: the N-way reduce of the device part.  When the call was
     # split, its launch is bracketed by the Evaluator's own events (fork ->
@@ -373,7 +394,9 @@ def main():
                       "algbw_GBs": w_ar.bytes_per_rank / (median(ar_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ar1), "split_calls_timed": int(split_samples)},
         "allgather": {"ms_median": median(ag_ms), "ms_p10": percentile(ag_ms, 0.1), "ms_p90": percentile(ag_ms, 0.9),
-                      "calls_timed": len(ag_ms),
+                      "calls_timed": len(ag_ms), "timing": "untimed leg after the timed region, same call sequence",
+                      "ms_per_call_in_batches_of_10": ag_batch_ms,
+                      "hbm_GBs_in_batches_of_10": ag_bytes / (ag_batch_ms * 1e-3) / 1e9,
                       "hbm_GBs": ag_bytes / (median(ag_ms) * 1e-3) / 1e9,
                       "algbw_GBs": N * w_ag.bytes_per_rank / (median(ag_ms) * 1e-3) / 1e9,
                       "host_units": host_units(s_ag1)},
