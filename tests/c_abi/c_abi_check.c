@@ -1,7 +1,8 @@
 /* A plain C program that drives the library through its C ABI with no Python
  * in between: 8 rank buffers in device memory, AllReduce (bf16 and f32) and
  * AllGather with the whole message on the device path and with 12 % of it on
- * the host-staged path, every result compared bit for bit with the CPU oracle.
+ * the host-staged path, and the AllReduce that needs no communicator, every
+ * result compared bit for bit with the CPU oracle.
  * Test infrastructure: built by tests/c_abi/build.py, run by the GPU tests.
  * Exit status 0 = every comparison passed. */
 #define __HIP_PLATFORM_AMD__ 1
@@ -138,6 +139,17 @@ int main(void) {
             snprintf(what, sizeof what, "allgather %s host share %u/10000", dtype == FLEX_F32 ? "f32" : "bf16",
                      shares[k]);
             failures += check(what, got, want_ag, N * count * es);
+        }
+        {
+            /* the entry point that needs no communicator and allocates nothing */
+            char what[96];
+            HIP_OK(hipMemsetAsync(out_ar, 0, count * es, stream));
+            FLEX_OK_OR_FAIL(flex_allreduce_staged_noalloc(dev_c, N, 3, out_ar, count, dtype, FLEX_SUM, 1200, stream));
+            HIP_OK(hipStreamSynchronize(stream));
+            HIP_OK(hipMemcpy(got, out_ar, count * es, hipMemcpyDeviceToHost));
+            snprintf(what, sizeof what, "allreduce %s without a communicator, staged share 1200/10000",
+                     dtype == FLEX_F32 ? "f32" : "bf16");
+            failures += check(what, got, want_ar, count * es);
         }
         flex_stats_t st;
         FLEX_OK_OR_FAIL(flex_evaluator_drain(comm));

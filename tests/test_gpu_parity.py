@@ -1174,5 +1174,5 @@ def test_plain_c_program_through_the_c_abi():
     run = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     say(run.stdout, run.stderr)
     assert run.returncode == 0, run.stdout + run.stderr
-    assert run.stdout.count("ok  ") == 8 and "C ABI check passed" in run.stdout
+    assert run.stdout.count("ok  ") == 10 and "C ABI check passed" in run.stdout
 
