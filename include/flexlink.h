@@ -349,8 +349,9 @@ int flex_config_default(flex_config_t* cfg);
  *   max_bytes_per_rank  largest per-rank message any later call will pass.
  *   cfg                 host pointer or NULL for defaults.
  * Allocates, once, per host path: num_slots pinned slots of (nranks-1) *
- * chunk_bytes, three side streams at default priority, slot events and, by
- * engine, device memory: FLEX_ENGINE_HYBRID num_slots staging buffers of the
+ * chunk_bytes, two side streams at default priority (FLEX_ENGINE_HYBRID: one
+ * per slot, or three with FLEX_SYNC_COUNTERS), slot events and, by engine,
+ * device memory: FLEX_ENGINE_HYBRID num_slots staging buffers of the
  * slot size; FLEX_ENGINE_SDMA a scratch of (nranks-1) * ceil(max_bytes_per_rank
  * * max_host_units / share_total) bytes (rounded up); FLEX_ENGINE_KERNEL none.
  * Plus one ring of timing events.  Nothing is allocated per call afterwards.

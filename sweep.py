@@ -237,7 +237,7 @@ def run_small():
            "back_to_back_us_per_call": per * 1e3, "back_to_back_hbm_GBs": c.hbm_bytes / per / 1e6,
            "graph_replay_us_per_call": per_graph * 1e3, "graph_replay_hbm_GBs": c.hbm_bytes / per_graph / 1e6,
            "rotating_64_buffer_sets_us_per_call": cold * 1e3, "rotating_hbm_GBs": c.hbm_bytes / cold / 1e6,
-           "note": "9 MiB of traffic per call: launch-bound; the warm figure is served by L2 / Infinity Cache"}
+           "note": "9 MiB of traffic per call: launch-bound; the warm figure is served by L2 and the memory-side cache"}
     c.close()
     return out
 
