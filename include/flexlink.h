@@ -90,7 +90,8 @@ enum flex_balancer_stage { FLEX_STAGE_TUNING = 1, FLEX_STAGE_RUNTIME = 2 };
  * ---------------------------------------------------------------------- */
 typedef struct flex_balancer_cfg {
     uint32_t share_total;          /* units the message is divided into (default 10000) */
-    uint32_t initial_step;         /* Algorithm 1 INITIAL_ADJUSTMENT_STEP, in units (default 64) */
+    uint32_t initial_step;         /* Algorithm 1 INITIAL_ADJUSTMENT_STEP, in units (default 16: on one GPU the
+                                      balanced host share is 30-90 units, a coarser step drains it in one move) */
     uint32_t stability_required;   /* Algorithm 1 STABILITY_REQUIRED (default 3) */
     uint32_t max_tune_iters;       /* Algorithm 1 loop bound (paper: 100) */
     uint32_t window;               /* Stage 2: calls per Evaluator window = Load Balancer period (default 10) */

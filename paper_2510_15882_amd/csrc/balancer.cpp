@@ -11,7 +11,7 @@ namespace flex {
 
 void balancer_cfg_default(flex_balancer_cfg_t* c) {
     c->share_total = 10000;
-    c->initial_step = 64;
+    c->initial_step = 16;
     c->stability_required = 3;
     c->max_tune_iters = 100;
     c->window = 10;

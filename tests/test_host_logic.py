@@ -42,7 +42,7 @@ def test_struct_layout_defaults_come_through():
     assert c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
     b = c.balancer
     assert (b.share_total, b.initial_step, b.stability_required, b.max_tune_iters, b.window,
-            b.runtime_step, b.aux_share_cap) == (10000, 64, 3, 100, 10, 4, 0)
+            b.runtime_step, b.aux_share_cap) == (10000, 16, 3, 100, 10, 4, 0)
     assert b.convergence_threshold == 0.05 and b.runtime_threshold == 0.10
     assert fx.flex_status_string(0) == "ok" and fx.flex_status_string(1) == "invalid argument"
 
