@@ -144,7 +144,28 @@ def cpu_baseline(oc, ar_host, ag_host, ar_bytes, ag_bytes, budget_s=10.0):
         oc.allgather(ag_host)
         single.append(time.perf_counter() - t0)
     oc.set_threads(threads)
+    # the single collectives, all cores, best of 5 (algorithmic bytes / time): configuration 2's AllReduce,
+    # configuration 1's AllGather, configuration 0's shape (1 MiB of f32 per rank, in cache) and a 64 MiB-per-rank
+    # slice standing in for the larger messages of configurations 3 and 4
+    def best(fn, n=5):
+        out = []
+        for _ in range(n):
+            t0 = time.perf_counter()
+            fn()
+            out.append(time.perf_counter() - t0)
+        return min(out)
+    import numpy as np
+    small = [np.linspace(-1.0, 1.0, 262144, dtype=np.float32) * (r + 1) / 8 for r in range(N)]
+    slice64 = [a[:32 << 20] for a in ar_host]
+    per_collective = {
+        "cfg2_allreduce_bf16_256MiB_GBs": ar_bytes / best(lambda: oc.allreduce(ar_host)) / 1e9,
+        "cfg1_allgather_bf16_32MiB_GBs": ag_bytes / best(lambda: oc.allgather(ag_host)) / 1e9,
+        "cfg0_allreduce_f32_1MiB_GBs": 9 * (1 << 20) / best(lambda: oc.allreduce(small), 20) / 1e9,
+        "allreduce_bf16_64MiB_per_rank_GBs": 9 * (64 << 20) / best(lambda: oc.allreduce(slice64)) / 1e9,
+        "allgather_bf16_64MiB_per_rank_GBs": 16 * (64 << 20) / best(lambda: oc.allgather(slice64)) / 1e9,
+    }
     return {"value": (ar_bytes + ag_bytes) / med / 1e9, "unit": "GB/s", "cores": threads,
+            "per_collective": per_collective,
             "single_thread": {"value": (ar_bytes + ag_bytes) / min(single) / 1e9, "unit": "GB/s",
                               "seconds_per_step": min(single), "passes": 3, "statistic": "best"},
             "kind": "oracle", "seconds_per_step": med, "best_seconds_per_step": min(times), "passes": len(times),
