@@ -197,6 +197,7 @@ def main():
                     help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
     ap.add_argument("--host-engine", type=int, default=-1, help="0 hybrid, 1 copy kernels, 2 DMA engines")
     ap.add_argument("--host-blocks", type=int, default=0)
+    ap.add_argument("--reduce-lds", type=int, default=-1, help="LDS bytes reserved per reduce workgroup (occupancy cap)")
     ap.add_argument("--max-host-units", type=int, default=0,
                     help="largest host share the communicator accepts (default 2500; 10000 to time the host path alone "
                          "with --mode static:10000)")
@@ -247,11 +248,12 @@ def main():
         cfg.max_host_units = args.max_host_units
     for key, val in (("reduce_nontemporal", args.reduce_nt), ("copy_nontemporal", args.copy_nt),
                      ("host_engine", args.host_engine), ("reduce_serial_loads", args.reduce_serial),
-                     ("launch_shape", args.launch_shape)):
+                     ("launch_shape", args.launch_shape), ("reduce_lds_reserve", args.reduce_lds)):
         if val >= 0:
             setattr(cfg, key, val)
     effective = {key: getattr(cfg, key) for key in (
-        "launch_shape", "reduce_serial_loads", "reduce_nontemporal", "copy_nontemporal", "host_engine", "host_blocks",
+        "launch_shape", "reduce_serial_loads", "reduce_nontemporal", "reduce_lds_reserve", "copy_nontemporal",
+        "host_engine", "host_blocks", "host_down_blocks",
         "host_die_shift", "chunk_bytes", "min_step_bytes", "num_slots")}
     comm = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg)
     stream = torch.cuda.Stream()

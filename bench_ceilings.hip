@@ -231,6 +231,13 @@ void hbm_ceilings(Json& out, int reps) {
                                (u32x4*)set[(k + 1) & 1], per);
         });
         rate("xor_8_reads_1_write_one_load_in_flight", (double)(kBlock + kSlice), ms);
+        // the same with 5632 bytes of (unused) LDS reserved per workgroup: a compute unit then holds 29
+        // wavefronts instead of 32
+        ms = time_launches(warm, reps, [&](int k) {
+            hipLaunchKernelGGL(k_xor8<true>, dim3((unsigned)(per / 64)), dim3(64), 5632, 0, (const u32x4*)set[k & 1],
+                               (u32x4*)set[(k + 1) & 1], per);
+        });
+        rate("xor_8_reads_1_write_one_load_in_flight_29_waves_per_cu", (double)(kBlock + kSlice), ms);
         ms = time_launches(warm, reps, [&](int k) {
             hipLaunchKernelGGL(k_xor8_all, dim3((unsigned)(per / 64)), dim3(64), 0, 0, (const u32x4*)set[k & 1],
                                (u32x4*)set[(k + 1) & 1], per);

@@ -59,6 +59,7 @@ class Config(_Struct):
                 ("max_host_units", u32), ("split_align_elems", u32), ("tune_reps", u32), ("probe_units", u32),
                 ("tune_accept_check", u32), ("accept_pairs", u32), ("launch_shape", u32),
                 ("reduce_serial_loads", u32), ("reduce_nontemporal", u32), ("copy_nontemporal", u32),
+                ("reduce_lds_reserve", u32), ("reserved", u32),
                 ("host_engine", u32), ("host_blocks", u32), ("host_die_shift", u32), ("min_step_bytes", u32),
                 ("slot_sync", u32), ("num_aux_paths", u32), ("host_down_blocks", u32), ("sample_every", u32),
                 ("balancer", BalancerCfg)]

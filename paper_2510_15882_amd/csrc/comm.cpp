@@ -864,6 +864,7 @@ int flex_config_default(flex_config_t* cfg) {
     cfg->launch_shape = FLEX_SHAPE_WAVE;
     cfg->reduce_serial_loads = 1;
     cfg->reduce_nontemporal = 3;
+    cfg->reduce_lds_reserve = 5632;
     cfg->copy_nontemporal = 3;
     cfg->host_engine = FLEX_ENGINE_KERNEL;
     cfg->host_blocks = 8;
@@ -899,7 +900,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     if (c.chunk_bytes < 4096 || c.chunk_bytes % 256 || c.num_slots < 1 || c.num_slots > 64 ||
         c.host_engine > FLEX_ENGINE_SDMA || c.slot_sync > FLEX_SYNC_COUNTERS || c.host_blocks < 1 ||
         c.host_blocks > 65536 || c.host_down_blocks < 1 || c.host_down_blocks > 65536 || c.sample_every < 1 || c.min_step_bytes == 0 || c.num_aux_paths < 1 || c.num_aux_paths > 2 ||
-        c.host_die_shift > 3 || c.reduce_serial_loads > 2 || c.launch_shape > FLEX_SHAPE_BLOCK ||
+        c.host_die_shift > 3 || c.reduce_serial_loads > 2 || c.reduce_lds_reserve > 65536 || c.launch_shape > FLEX_SHAPE_BLOCK ||
         !hints_ok(c.reduce_nontemporal) || !hints_ok(c.copy_nontemporal) || b.share_total == 0 ||
         c.max_host_units > b.share_total || c.split_align_elems == 0 || c.tune_reps < 1 || c.accept_pairs < 1 ||
         c.probe_units == 0 || b.window == 0 || b.initial_step == 0 || b.runtime_step == 0)
@@ -932,6 +933,7 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     m->reduce_shape.serial_min_tiles = c.reduce_serial_loads == 2 ? 1u
                                        : c.reduce_serial_loads == 1 ? 16u * (uint32_t)cus : 0u;
     m->copy_shape = {threads, 1, c.copy_nontemporal, (uint32_t)cus, 0};
+    m->reduce_shape.serial_lds_bytes = c.reduce_lds_reserve;
     // kernels that read or write pinned memory over PCIe: a fixed, small number
     // of workgroups striding over the step, kept on few dies, so that waves
     // waiting on the link do not crowd the device path off the memory system

@@ -97,11 +97,11 @@ __global__ void gather_copy_kernel(CopyArgs a) {
 
 // Streaming hints: 0 none, 1 non-temporal loads, 3 non-temporal loads and stores.
 template <int UNROLL>
-int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
+int launch_one(const CopyArgs& a, dim3 grid, uint32_t threads, uint32_t nt, uint32_t lds, hipStream_t stream) {
     switch (nt) {
-        case 0: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, false>), grid, dim3(threads), 0, stream, a); break;
-        case 1: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, false>), grid, dim3(threads), 0, stream, a); break;
-        default: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, true>), grid, dim3(threads), 0, stream, a); break;
+        case 0: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, false, false>), grid, dim3(threads), lds, stream, a); break;
+        case 1: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, false>), grid, dim3(threads), lds, stream, a); break;
+        default: hipLaunchKernelGGL((gather_copy_kernel<UNROLL, true, true>), grid, dim3(threads), lds, stream, a); break;
     }
     return (int)hipGetLastError();
 }
@@ -138,10 +138,10 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;
     switch (unroll) {
-        case 2: return launch_one<2>(a, grid, threads, shape.nontemporal, s);
-        case 4: return launch_one<4>(a, grid, threads, shape.nontemporal, s);
-        case 6: return launch_one<6>(a, grid, threads, shape.nontemporal, s);
-        default: return launch_one<1>(a, grid, threads, shape.nontemporal, s);
+        case 2: return launch_one<2>(a, grid, threads, shape.nontemporal, shape.lds_bytes, s);
+        case 4: return launch_one<4>(a, grid, threads, shape.nontemporal, shape.lds_bytes, s);
+        case 6: return launch_one<6>(a, grid, threads, shape.nontemporal, shape.lds_bytes, s);
+        default: return launch_one<1>(a, grid, threads, shape.nontemporal, shape.lds_bytes, s);
     }
 }
 

@@ -220,33 +220,34 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
 
 // Streaming hints: 0 none, 1 non-temporal loads, 3 non-temporal loads and stores.
 template <int N, int DT, bool SERIAL>
-int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t nt, hipStream_t stream) {
+int launch_one(const ReduceArgs& a, uint32_t grid, uint32_t threads, uint32_t nt, uint32_t lds, hipStream_t stream) {
     switch (nt) {
-        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, false, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, false>), dim3(grid), dim3(threads), 0, stream, a); break;
-        default: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, true>), dim3(grid), dim3(threads), 0, stream, a); break;
+        case 0: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, false, false>), dim3(grid), dim3(threads), lds, stream, a); break;
+        case 1: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, false>), dim3(grid), dim3(threads), lds, stream, a); break;
+        default: hipLaunchKernelGGL((reduce_n_kernel<N, DT, SERIAL, true, true>), dim3(grid), dim3(threads), lds, stream, a); break;
     }
     return (int)hipGetLastError();
 }
 
 template <int N, int DT>
-int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, bool serial, uint32_t nt, hipStream_t stream) {
-    return serial ? launch_one<N, DT, true>(a, grid, threads, nt, stream)
-                  : launch_one<N, DT, false>(a, grid, threads, nt, stream);
+int launch_n(const ReduceArgs& a, uint32_t grid, uint32_t threads, bool serial, uint32_t nt, uint32_t lds,
+             hipStream_t stream) {
+    return serial ? launch_one<N, DT, true>(a, grid, threads, nt, lds, stream)
+                  : launch_one<N, DT, false>(a, grid, threads, nt, lds, stream);
 }
 
 template <int DT>
 int launch_dtype(int n, const ReduceArgs& a, uint32_t grid, uint32_t threads, bool serial, uint32_t nt,
-                 hipStream_t stream) {
+                 uint32_t lds, hipStream_t stream) {
     switch (n) {
-        case 1: return launch_n<1, DT>(a, grid, threads, serial, nt, stream);
-        case 2: return launch_n<2, DT>(a, grid, threads, serial, nt, stream);
-        case 3: return launch_n<3, DT>(a, grid, threads, serial, nt, stream);
-        case 4: return launch_n<4, DT>(a, grid, threads, serial, nt, stream);
-        case 5: return launch_n<5, DT>(a, grid, threads, serial, nt, stream);
-        case 6: return launch_n<6, DT>(a, grid, threads, serial, nt, stream);
-        case 7: return launch_n<7, DT>(a, grid, threads, serial, nt, stream);
-        default: return launch_n<8, DT>(a, grid, threads, serial, nt, stream);
+        case 1: return launch_n<1, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 2: return launch_n<2, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 3: return launch_n<3, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 4: return launch_n<4, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 5: return launch_n<5, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 6: return launch_n<6, DT>(a, grid, threads, serial, nt, lds, stream);
+        case 7: return launch_n<7, DT>(a, grid, threads, serial, nt, lds, stream);
+        default: return launch_n<8, DT>(a, grid, threads, serial, nt, lds, stream);
     }
 }
 
@@ -292,12 +293,23 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     if (grid > (0x7fffffffull >> a.shift)) grid = 0x7fffffffull >> a.shift;
     grid <<= a.shift;
 
+    // With one load in flight per wavefront a compute unit that holds its full 32
+    // wavefronts runs 3-4 % slower than one that holds 25-31, once the launch is long
+    // enough to reach a steady state and has three or more inputs (measured on MI355X:
+    // +3.4 % at 8 x 256 MiB, +2.3 % at 4 x 256 MiB, +0.9 % at 3 x 256 MiB, but -3.8 %
+    // with two inputs and -3 % at 8 x 32 MiB; the all-in-flight schedule and the copy
+    // kernel lose with it at every size).  A small LDS reservation per workgroup, which
+    // the kernel never touches, keeps the count just below the limit for such launches:
+    // those that read at least cap_min_tiles_per_cu tiles per compute unit.
+    const uint64_t tiles_read = (uint64_t)(n + 1) * ((a.nvec + 63) / 64);
+    const bool cap = serial && n >= 3 && tiles_read >= (uint64_t)shape.cap_min_tiles_per_cu * shape.num_cus;
+    const uint32_t lds = cap ? shape.serial_lds_bytes : shape.lds_bytes;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)
-        return launch_dtype<kBF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
+        return launch_dtype<kBF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, lds, s);
     if (dtype == FLEX_F16)
-        return launch_dtype<kF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
-    return launch_dtype<kF32>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, s);
+        return launch_dtype<kF16>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, lds, s);
+    return launch_dtype<kF32>(n, a, (uint32_t)grid, threads, serial, shape.nontemporal, lds, s);
 }
 
 }  // namespace flex

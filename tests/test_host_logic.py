@@ -37,7 +37,7 @@ def test_struct_layout_defaults_come_through():
     assert c.split_align_elems == 2048 and c.min_split_bytes == 64 << 10
     assert c.tune_reps == 5 and c.probe_units == 200 and c.reduce_nontemporal == 3 and c.copy_nontemporal == 3
     assert (c.host_engine, c.host_blocks, c.host_down_blocks, c.min_step_bytes) == (fx.FLEX_ENGINE_KERNEL, 8, 6, 256 << 10)
-    assert c.sample_every == 1
+    assert c.sample_every == 1 and c.reduce_lds_reserve == 5632
     assert c.tune_accept_check == 1 and c.accept_pairs == 3 and c.launch_shape == fx.FLEX_SHAPE_WAVE
     assert c.slot_sync == 0 and c.num_aux_paths == 1 and c.host_die_shift == 2 and c.reduce_serial_loads == 1
     b = c.balancer
