@@ -942,6 +942,56 @@ def test_config3_sweep_point_under_its_own_protocol(collective, mib):
             checker.check(out, [st.last_split], "host path live, after 3 windows")
 
 
+def test_messages_beyond_32_bit_element_counts_and_byte_offsets():
+    # Two ranks of 2^31 + 2^26 + 37 bf16 elements (4 GiB + 128 MiB + 74 bytes each): element
+    # indexes pass 2^31, byte offsets pass 2^32, and the AllGather's second slice starts
+    # beyond 4 GiB.  Device path and a 1 % static split (the cut then lies beyond both
+    # limits, so the host path's pieces start there), checked against the oracle on
+    # windows at both ends, across 2^31 elements, across the cut and at random places.
+    count = (1 << 31) + (1 << 26) + 37
+    dtype = torch.bfloat16
+    piece = 1 << 28
+    bufs = []
+    for r in range(2):
+        t = torch.empty(count, dtype=dtype, device=DEV)
+        for k, a in enumerate(range(0, count, piece)):
+            wl.fill_rank(t[a:a + piece], "normal", 1.0, wl.rank_seed(9, r) + 100 * k)
+        bufs.append(t)
+    say("generated 2 x", count, "elements")
+    landmarks = [1 << 31, (1 << 31) + 1024, count - 37]
+
+    def windows(cut):
+        return sampled_windows(count, [c for c in landmarks + [cut] if c], nwin=16, width=1 << 15)
+
+    with Comm(nranks=2, rank=1, max_bytes=2 * count) as comm:
+        out = torch.zeros(count, dtype=dtype, device=DEV)
+        for units in (0, 100):
+            out.zero_()
+            fx.flex_set_split(comm, fx.FLEX_ALLREDUCE, fx.FLEX_SPLIT_STATIC, units)
+            fx.flex_allreduce_local(comm, bufs, out)
+            torch.cuda.synchronize()
+            cut = fx.flex_get_stats(comm, fx.FLEX_ALLREDUCE, count, dtype).last_split
+            assert cut == op.partition(count, units, 10000, 2048, (64 << 10) // 2)
+            assert units == 0 or (1 << 31) < cut < count
+            for a, b in windows(cut):
+                assert_same_bits(out[a:b], oracle_allreduce([x[a:b] for x in bufs]), "AR %d units, window %d" % (units, a))
+            say("allreduce", units, "units ok, cut", cut)
+        del out
+        out = torch.zeros(2 * count, dtype=dtype, device=DEV)
+        for units in (0, 100):
+            out.zero_()
+            fx.flex_set_split(comm, fx.FLEX_ALLGATHER, fx.FLEX_SPLIT_STATIC, units)
+            fx.flex_allgather_local(comm, bufs, out)
+            torch.cuda.synchronize()
+            cut = fx.flex_get_stats(comm, fx.FLEX_ALLGATHER, count, dtype).last_split
+            assert cut == op.partition(count, units, 10000, 2048, (64 << 10) // 2)
+            for a, b in windows(cut):
+                got = torch.cat([out[r * count + a:r * count + b] for r in range(2)])
+                want = oracle_allgather([x[a:b] for x in bufs])
+                assert np.array_equal(wl.to_numpy_bits(got), want), "AG %d units, window %d" % (units, a)
+            say("allgather", units, "units ok, cut", cut)
+
+
 def test_config4_prefill_allreduce_adaptive_50_calls():
     w = wl.config(4)
     say("generating", w.name)
