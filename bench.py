@@ -195,7 +195,7 @@ def main():
     ap.add_argument("--copy-nt", type=int, default=-1)
     ap.add_argument("--reduce-serial", type=int, default=-1,
                     help="2: one load in flight per wavefront; 0: all of a tile; 1: by message size")
-    ap.add_argument("--host-engine", type=int, default=-1, help="0 hybrid, 1 copy kernels, 2 DMA engines")
+    ap.add_argument("--host-engine", type=int, default=-1, help="0 copy kernels, 1 hybrid (copy kernel up, DMA down), 2 DMA engines")
     ap.add_argument("--host-blocks", type=int, default=0)
     ap.add_argument("--reduce-lds", type=int, default=-1, help="LDS bytes reserved per reduce workgroup (occupancy cap)")
     ap.add_argument("--max-host-units", type=int, default=0,
