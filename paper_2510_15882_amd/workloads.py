@@ -66,6 +66,26 @@ def sweep_workloads(dtype_name="bf16"):
     return out
 
 
+GRID_RANKS = (2, 4, 8)
+GRID_MIB = (32, 64, 128, 256)
+
+
+def evaluation_grid_workloads():
+    """The grid of the paper's end-to-end table (Evaluation, Table 2): AllReduce
+    and AllGather on 2, 4 and 8 ranks with messages of 32..256 MiB, bf16 N(0,1).
+    The message size is the collective's buffer size as nccl-tests counts it:
+    every rank's whole buffer for AllReduce, the gathered output for AllGather
+    (each rank contributes 1/N of it), as in configuration 1."""
+    out = []
+    for coll in ("allreduce", "allgather"):
+        for nranks in GRID_RANKS:
+            for mib in GRID_MIB:
+                count = mib * MIB // 2 // (nranks if coll == "allgather" else 1)
+                out.append(Workload(5, "%s_bf16_%dranks_%dMiB" % (coll, nranks, mib), coll, torch.bfloat16,
+                                    count, "normal", 1.0, nranks))
+    return out
+
+
 def config(index: int) -> Workload:
     for w in CONFIGS:
         if w.index == index:

@@ -8,6 +8,7 @@ writes the figures as a plain-text table.
     python sweep.py --config 3 --dtype f32   # same byte sizes in binary32 (or f16)
     python sweep.py --config 4      # 65536 x 5120 bf16 AllReduce, 50 calls
     python sweep.py --config 0      # 1 MiB fp32 AllReduce: latency
+    python sweep.py --config 5      # the paper's evaluation grid: 2 / 4 / 8 ranks x 32..256 MiB, AR and AG
 
 Per case: Stage 1 on the hardware (rates of both paths, bandwidth-proportional
 initial shares, Algorithm 1, acceptance check), then adaptive calls (Stage 2),
@@ -26,9 +27,6 @@ import torch
 
 from paper_2510_15882_amd import binding as fx
 from paper_2510_15882_amd import workloads as wl
-
-N = 8
-
 
 def median(v):
     v = sorted(v)
@@ -57,10 +55,11 @@ class Case:
         es = self.bufs[0].element_size()
         self.is_ar = w.collective == "allreduce"
         self.coll = fx.FLEX_ALLREDUCE if self.is_ar else fx.FLEX_ALLGATHER
-        self.out = torch.empty(w.count if self.is_ar else N * w.count, dtype=w.dtype, device=dev)
-        self.hbm_bytes = (N + 1) * w.count * es if self.is_ar else 2 * N * w.count * es
-        self.alg_bytes = w.count * es if self.is_ar else N * w.count * es
-        self.comm = fx.flex_comm_create(N, 0, w.count * es, cfg)
+        n = w.nranks
+        self.out = torch.empty(w.count if self.is_ar else n * w.count, dtype=w.dtype, device=dev)
+        self.hbm_bytes = (n + 1) * w.count * es if self.is_ar else 2 * n * w.count * es
+        self.alg_bytes = w.count * es if self.is_ar else n * w.count * es
+        self.comm = fx.flex_comm_create(n, 0, w.count * es, cfg)
         self.stream = torch.cuda.Stream()
         torch.cuda.synchronize()
 
@@ -100,7 +99,7 @@ def live_ab(c, w, units, blocks=12, per_block=10):
     a, d = median(live_ms), median(device_ms)
     noise = 3 * max(mad(live_ms), mad(device_ms))
     # what PCIe could carry while the device path handles the rest, at 45 GB/s each way
-    pcie_share = (d * 1e-3) * 45e9 / ((N - 1) * w.count * c.bufs[0].element_size())
+    pcie_share = (d * 1e-3) * 45e9 / ((w.nranks - 1) * w.count * c.bufs[0].element_size())
     return {"host_share_units_start": units, "host_share_units_end": int(st.balancer.shares[1]),
             "live_ms": a, "device_only_ms": d, "mad_ms": [mad(live_ms), mad(device_ms)], "calls_each": len(live_ms),
             "gain_ms": d - a, "three_mad_ms": noise, "live_faster": bool(d - a > noise),
@@ -150,6 +149,51 @@ def run_case(w, windows=20, cfg=None):
         units = res.balanced_shares[1] or res.initial_shares[1] or 20
         out["host_path_forced_live"] = live_ab(c, w, units)
     c.close()
+    return out
+
+
+def run_grid_case(w, windows=5):
+    """One point of the paper's evaluation grid: the sweep's protocol with fewer
+    windows, plus the device path over rotating buffer sets (small messages
+    would otherwise be served by the memory-side cache)."""
+    out = run_case(w, windows=windows)
+    out["nranks"] = w.nranks
+    c = Case(w)
+    per_set = c.hbm_bytes
+    nsets = min(12, max(2, -(-(3 << 29) // per_set)))
+    sets = [(c.bufs, c.out)] + [(wl.make_rank_buffers(w, "cuda:0"), torch.empty_like(c.out)) for _ in range(nsets - 1)]
+    call = fx.flex_allreduce_local if c.is_ar else fx.flex_allgather_local
+    fx.flex_set_split(c.comm, c.coll, fx.FLEX_SPLIT_STATIC, 0)
+    reps = 5 * nsets
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    with torch.cuda.stream(c.stream):
+        for k in range(nsets):
+            call(c.comm, sets[k][0], sets[k][1], stream=c.stream)
+        for k, (a, b) in enumerate(evs):
+            bufs, dst = sets[k % nsets]
+            a.record(c.stream)
+            call(c.comm, bufs, dst, stream=c.stream)
+            b.record(c.stream)
+        # the same calls with one event pair around all of them: events around a call of
+        # 15-50 us add 2-3 us to it
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(c.stream)
+        for k in range(reps):
+            call(c.comm, sets[k % nsets][0], sets[k % nsets][1], stream=c.stream)
+        e1.record(c.stream)
+    c.stream.synchronize()
+    ms = [a.elapsed_time(b) for a, b in evs]
+    batch = e0.elapsed_time(e1) / reps
+    out["rotating_buffer_sets"] = nsets
+    out["rotating_ms"] = median(ms)
+    out["rotating_hbm_GBs"] = c.hbm_bytes / median(ms) / 1e6
+    out["rotating_algbw_GBs"] = c.alg_bytes / median(ms) / 1e6
+    out["rotating_batch_ms_per_call"] = batch
+    out["rotating_batch_hbm_GBs"] = c.hbm_bytes / batch / 1e6
+    out["rotating_batch_algbw_GBs"] = c.alg_bytes / batch / 1e6
+    out["rotating_batch_calls"] = reps
+    c.close()
+    del sets
     return out
 
 
@@ -250,7 +294,8 @@ def summary_lines(r):
                 % (r["case"], r["event_bracketed_single_call_us"], r["back_to_back_us_per_call"],
                    r["back_to_back_hbm_GBs"], r["graph_replay_us_per_call"], r["graph_replay_hbm_GBs"],
                    r["rotating_64_buffer_sets_us_per_call"], r["rotating_hbm_GBs"])]
-    lines = ["cfg%d %s (%g MiB per rank)" % (r["config"], r["case"], r["MiB_per_rank"]),
+    lines = ["%s %s (%g MiB per rank)" % ("grid" if r["config"] == 5 else "cfg%d" % r["config"], r["case"],
+                                          r["MiB_per_rank"]),
              "  path rates (message GB/s) device %.1f, host %.2f; InitializeShares host %.2f %%; Algorithm 1: %s "
              "iterations, balanced host share %.2f %%"
              % (r["path_rate_GBs"][0], r["path_rate_GBs"][1], r["initial_host_share_pct"],
@@ -271,6 +316,12 @@ def summary_lines(r):
                      % (r["adaptive_ms_per_call"], r["adaptive_hbm_GBs"], r["adaptive_algbw_GBs"],
                         r["device_only_ms_per_call"], r["device_only_hbm_GBs"], r["host_share_pct_after"],
                         r["blocking_reads"]))
+    if "rotating_ms" in r:
+        lines.append("  device path over %d rotating buffer sets: events around each call %.4f ms, HBM %.0f GB/s, algbw "
+                     "%.1f GB/s; %d calls between one pair of events %.4f ms per call, HBM %.0f GB/s, algbw %.1f GB/s"
+                     % (r["rotating_buffer_sets"], r["rotating_ms"], r["rotating_hbm_GBs"], r["rotating_algbw_GBs"],
+                        r["rotating_batch_calls"], r["rotating_batch_ms_per_call"], r["rotating_batch_hbm_GBs"],
+                        r["rotating_batch_algbw_GBs"]))
     live = r.get("host_path_forced_live")
     if live:
         lines.append("  host path forced live at %d units (ends at %d): %.4f ms (MAD %.4f) vs device-only %.4f ms (MAD %.4f), "
@@ -286,7 +337,8 @@ def summary_lines(r):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[0, 3, 4])
+    ap.add_argument("--config", type=int, required=True, choices=[0, 3, 4, 5],
+                    help="0, 3, 4: the configurations; 5: the paper's evaluation grid (2 / 4 / 8 ranks x 32..256 MiB)")
     ap.add_argument("--summary", default=None, help="append the cases as plain text to this file")
     ap.add_argument("--windows", type=int, default=20)
     ap.add_argument("--max-mib", type=int, default=1024)
@@ -306,6 +358,11 @@ def main():
         emit(run_small())
     elif args.config == 4:
         emit(run_prefill())
+    elif args.config == 5:
+        for w in wl.evaluation_grid_workloads():
+            log("case", w.name)
+            emit(run_grid_case(w, windows=min(args.windows, 5)))
+            torch.cuda.empty_cache()
     else:
         for w in wl.sweep_workloads(args.dtype):
             if w.bytes_per_rank > args.max_mib * wl.MIB:

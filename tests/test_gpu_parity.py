@@ -942,6 +942,62 @@ def test_config3_sweep_point_under_its_own_protocol(collective, mib):
             checker.check(out, [st.last_split], "host path live, after 3 windows")
 
 
+@pytest.mark.parametrize("w", wl.evaluation_grid_workloads(), ids=lambda w: w.name)
+def test_evaluation_grid_point(w):
+    # One point of the paper's end-to-end grid (Evaluation, Table 2: AllReduce and AllGather
+    # on 2, 4 and 8 ranks, 32..256 MiB) at full size, element by element: after Stage 1 on
+    # the hardware (replayed through the oracle balancer), after a window of adaptive calls,
+    # and with a static 5 % split so that the host path is live whatever Stage 1 decided.
+    say("generating", w.name)
+    n = w.nranks
+    bufs = wl.make_rank_buffers(w, DEV)
+    is_ar = w.collective == "allreduce"
+    coll = fx.FLEX_ALLREDUCE if is_ar else fx.FLEX_ALLGATHER
+    host = [wl.to_numpy_bits(b) for b in bufs]
+    want = oc.allreduce(host) if is_ar else oc.allgather(host)
+    del host
+    cfg = fx.flex_config_default()
+
+    def check(out, what):
+        if is_ar:
+            assert_same_bits(out, want, what)
+        else:
+            assert np.array_equal(wl.to_numpy_bits(out), want), what
+
+    with Comm(nranks=n, rank=n - 1, max_bytes=w.bytes_per_rank) as comm:
+        out = torch.zeros(w.count if is_ar else n * w.count, dtype=w.dtype, device=DEV)
+
+        def call():
+            if is_ar:
+                fx.flex_allreduce_local(comm, bufs, out)
+            else:
+                fx.flex_allgather_local(comm, bufs, out)
+
+        res = fx.flex_comm_tune(comm, coll, bufs, out)
+        torch.cuda.synchronize()
+        check(out, "after tune")
+        check_stage1_against_oracle(comm, coll, w.count, w.dtype, res, cfg)
+        say(w.name, "host share: initial", res.initial_shares[1], "balanced", res.balanced_shares[1],
+            "kept" if not res.reverted else "reverted")
+
+        fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_ADAPTIVE)
+        twin = Stage2Twin(comm, coll, w.count, w.dtype, cfg)
+        for k in range(cfg.balancer.window):
+            if k == cfg.balancer.window - 1:
+                out.zero_()
+            call()
+            twin.after_call()
+        check(out, "after a window of adaptive calls")
+
+        out.zero_()
+        fx.flex_set_split(comm, coll, fx.FLEX_SPLIT_STATIC, 500)
+        call()
+        torch.cuda.synchronize()
+        st = fx.flex_get_stats(comm, coll, w.count, w.dtype)
+        assert st.last_split == op.partition(w.count, 500, 10000, 2048, (64 << 10) // out.element_size()) < w.count
+        check(out, "static 5 % split")
+
+
 def test_messages_beyond_32_bit_element_counts_and_byte_offsets():
     # Two ranks of 2^31 + 2^26 + 37 bf16 elements (4 GiB + 128 MiB + 74 bytes each): element
     # indexes pass 2^31, byte offsets pass 2^32, and the AllGather's second slice starts

@@ -18,6 +18,15 @@ def test_configs_have_the_stated_shapes():
         assert all(w.dtype == dt and name in w.name for w in other)
 
 
+def test_evaluation_grid_has_the_sizes_of_the_paper_s_table():
+    grid = wl.evaluation_grid_workloads()
+    assert len(grid) == 24 and {w.nranks for w in grid} == {2, 4, 8}
+    for w in grid:
+        message = w.bytes_per_rank * (w.nranks if w.collective == "allgather" else 1)
+        assert message >> 20 in (32, 64, 128, 256) and message % (1 << 20) == 0
+        assert len(wl.make_rank_buffers(w, count=16)) == w.nranks
+
+
 def test_generation_is_reproducible_and_rank_distinct():
     a = wl.make_rank_buffers(wl.config(2), count=4096)
     b = wl.make_rank_buffers(wl.config(2), count=4096)
