@@ -261,20 +261,20 @@ typedef struct flex_config {
     uint32_t reduce_serial_loads;/* device-path reduce kernel.  2 = a wavefront keeps one load in flight and asks
                                     for input r+1 only when input r has arrived; 0 = all N loads of a tile are
                                     issued before the first add; 1 (default) = the first for launches of at
-                                    least 16 tiles per compute unit (4 MiB of bf16 per rank on MI355X), the
-                                    second for shorter ones */
+                                    least 16 tiles per compute unit (4 MiB of bf16 per rank on MI355X) with
+                                    three or more ranks, the second for shorter ones and for two ranks */
     uint32_t reduce_nontemporal; /* streaming hints of the reduce kernel: 0 none, 1 non-temporal loads,
                                     3 (default) non-temporal loads and stores.  Plain stores let a reused
                                     output stay in the 256 MB memory-side cache (an nccl-tests style loop) */
     uint32_t copy_nontemporal;   /* same for the copy kernel */
     uint32_t reduce_lds_reserve; /* bytes of LDS reserved per workgroup of the device-path reduce kernel when it
-                                    takes the one-load-in-flight schedule on a long launch (three or more
+                                    takes the one-load-in-flight schedule on a long launch (four or more
                                     ranks, at least 2 MiB read per compute unit: 57 MiB of bf16 per rank with
                                     8 ranks).  Default 5632; 0 = none.  The kernel uses no LDS: the reservation
                                     caps the wavefronts a compute unit holds at 160 KiB / reserve = 29 instead
-                                    of 32, which on MI355X makes such launches 3-4 % faster (any value from
-                                    5200 to 6400 does; short launches, two ranks, the all-in-flight schedule
-                                    and the copy kernel lose with it and are launched without) */
+                                    of 32, which on MI355X makes such launches 2-4 % faster (any value from
+                                    5200 to 6400 does; short launches, two and three ranks, the all-in-flight
+                                    schedule and the copy kernel lose with it and are launched without) */
     uint32_t reserved;
     uint32_t host_engine;        /* flex_host_engine of the first host path (default FLEX_ENGINE_KERNEL; the
                                     engine with hipMemcpyAsync in both directions is FLEX_ENGINE_SDMA) */

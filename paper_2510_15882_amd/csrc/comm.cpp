@@ -932,6 +932,8 @@ int flex_comm_create(flex_comm_t** comm, int nranks, int rank, size_t max_bytes_
     // 16 tiles per compute unit: half of the wavefront slots of the chip
     m->reduce_shape.serial_min_tiles = c.reduce_serial_loads == 2 ? 1u
                                        : c.reduce_serial_loads == 1 ? 16u * (uint32_t)cus : 0u;
+    // left to itself the library keeps both loads of a two-rank sum in flight at every size
+    m->reduce_shape.serial_min_inputs = c.reduce_serial_loads == 1 ? 3u : 1u;
     m->copy_shape = {threads, 1, c.copy_nontemporal, (uint32_t)cus, 0};
     m->reduce_shape.serial_lds_bytes = c.reduce_lds_reserve;
     // kernels that read or write pinned memory over PCIe: a fixed, small number

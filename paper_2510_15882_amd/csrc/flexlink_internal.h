@@ -127,17 +127,19 @@ struct LaunchShape {
     // workgroup works: 3 keeps the working workgroups on one of the 8 dies.
     uint32_t block_shift = 0;
     // Reduce kernel: a launch of at least this many wavefront tiles (1 KiB per
-    // input) keeps one load in flight per wavefront instead of all of a tile's
-    // loads (0 = never).
+    // input) and at least serial_min_inputs inputs keeps one load in flight per
+    // wavefront instead of all of a tile's loads (0 tiles = never).
     uint32_t serial_min_tiles = 0;
+    uint32_t serial_min_inputs = 1;
     // Bytes of LDS reserved per workgroup.  The kernels use no LDS: the reservation
     // only caps how many workgroups a compute unit holds at once (160 KiB / lds_bytes).
     uint32_t lds_bytes = 0;
     // Reduce kernel: the reservation used instead when a launch takes the serial
-    // load schedule, has at least three inputs and reads (inputs + output) at least
-    // cap_min_tiles_per_cu wavefront tiles of 1 KiB per compute unit.
+    // load schedule, has at least cap_min_inputs inputs and reads (inputs + output)
+    // at least cap_min_tiles_per_cu wavefront tiles of 1 KiB per compute unit.
     uint32_t serial_lds_bytes = 0;
     uint32_t cap_min_tiles_per_cu = 2048;  // 8 inputs: 57 MiB of bf16 per rank on 256 compute units
+    uint32_t cap_min_inputs = 4;
 };
 
 // Enqueue out[i] = sum over r (rank order) of in[r][i], i in [0, count), on

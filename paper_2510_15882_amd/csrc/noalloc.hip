@@ -88,6 +88,7 @@ extern "C" int flex_allreduce_staged_noalloc(const void* const* rank_bufs, int n
     hipStream_t stream = (hipStream_t)hip_stream;
     flex::LaunchShape reduce_shape{64, 1, 3, (uint32_t)cus, 0};
     reduce_shape.serial_min_tiles = 16u * (uint32_t)cus;
+    reduce_shape.serial_min_inputs = 3;
     reduce_shape.serial_lds_bytes = 5632;  // the library's default occupancy cap for this schedule
     const flex::LaunchShape staged_reduce_shape{256, 1, 0, (uint32_t)cus, 0};
     const flex::LaunchShape staged_copy_shape{256, 2, 0, (uint32_t)cus, 0};

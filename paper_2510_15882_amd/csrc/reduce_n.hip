@@ -281,8 +281,11 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     const uint32_t threads = shape.threads;
     // The serial schedule pays N load latencies per tile: it wins once the
     // message keeps every wavefront slot of the chip busy several times over,
-    // and loses on short messages whose time is one wavefront's lifetime.
-    const bool serial = shape.serial_min_tiles && (a.nvec + 63) / 64 >= shape.serial_min_tiles;  // 1 KiB tiles
+    // and loses on short messages whose time is one wavefront's lifetime.  With
+    // two inputs it loses at every size (measured on MI355X, 2 x 32 MiB ... 2 x 1 GiB
+    // of bf16: 1-5 % behind both loads in flight), which serial_min_inputs expresses.
+    const bool serial = shape.serial_min_tiles && (uint32_t)n >= shape.serial_min_inputs &&
+                        (a.nvec + 63) / 64 >= shape.serial_min_tiles;  // 1 KiB tiles
     const uint64_t ntiles = (a.nvec + threads - 1) / threads;
     const uint64_t nscalar = count - a.nvec * vec_elems;
     const uint64_t scalar_blocks = (nscalar + threads - 1) / threads;
@@ -295,14 +298,16 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
 
     // With one load in flight per wavefront a compute unit that holds its full 32
     // wavefronts runs 3-4 % slower than one that holds 25-31, once the launch is long
-    // enough to reach a steady state and has three or more inputs (measured on MI355X:
-    // +3.4 % at 8 x 256 MiB, +2.3 % at 4 x 256 MiB, +0.9 % at 3 x 256 MiB, but -3.8 %
-    // with two inputs and -3 % at 8 x 32 MiB; the all-in-flight schedule and the copy
-    // kernel lose with it at every size).  A small LDS reservation per workgroup, which
-    // the kernel never touches, keeps the count just below the limit for such launches:
-    // those that read at least cap_min_tiles_per_cu tiles per compute unit.
+    // enough to reach a steady state and has four or more inputs (measured on MI355X:
+    // +3 % at 8 x 256 MiB, +2 % at 4 x 256 MiB, +4 % at 4 x 1 GiB, but -1 to -2 % at
+    // 3 x 128 and 3 x 256 MiB, -1 % with two inputs and -3 % at 8 x 32 MiB; the
+    // all-in-flight schedule and the copy kernel lose with it at every size).  A small
+    // LDS reservation per workgroup, which the kernel never touches, keeps the count
+    // just below the limit for such launches: those that read at least
+    // cap_min_tiles_per_cu tiles per compute unit.
     const uint64_t tiles_read = (uint64_t)(n + 1) * ((a.nvec + 63) / 64);
-    const bool cap = serial && n >= 3 && tiles_read >= (uint64_t)shape.cap_min_tiles_per_cu * shape.num_cus;
+    const bool cap = serial && (uint32_t)n >= shape.cap_min_inputs &&
+                     tiles_read >= (uint64_t)shape.cap_min_tiles_per_cu * shape.num_cus;
     const uint32_t lds = cap ? shape.serial_lds_bytes : shape.lds_bytes;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == FLEX_BF16)

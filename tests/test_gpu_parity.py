@@ -336,11 +336,11 @@ def test_every_launch_shape_gives_the_same_bits(shape, nt):
 @pytest.mark.parametrize("reserve", [0, 5632, 40000])
 def test_occupancy_cap_of_long_reduce_launches_does_not_change_the_bits(reserve):
     # long launches of the one-load-in-flight schedule reserve LDS they never use, only to
-    # hold fewer wavefronts per compute unit; 96 MiB per rank with 8 and with 3 ranks takes
-    # that path (2 ranks never do)
+    # hold fewer wavefronts per compute unit; 96 MiB per rank with 8 and with 4 ranks takes
+    # that path (3 and 2 ranks never do; 2 ranks keep both loads in flight)
     count = 48 * wl.MIB + 2048 + 3
     bufs = wl.make_rank_buffers(wl.config(2), DEV, count=count)
-    for nranks in (8, 3, 2):
+    for nranks in (8, 4, 3, 2):
         want = oracle_allreduce(bufs[:nranks])
         with Comm(nranks=nranks, max_bytes=count * 2, reduce_lds_reserve=reserve) as comm:
             out = torch.zeros(count, dtype=torch.bfloat16, device=DEV)
