@@ -458,6 +458,22 @@ def main():
         extras["warm_same_buffers_plain_stores"] = {
             "allreduce_ms": d, "allreduce_hbm_GBs": ar_bytes / d / 1e6,
             "note": "reduce_nontemporal = 1: the reused output stays in the memory-side cache, its stores never reach HBM"}
+        # the reduce kernel's occupancy cap on this machine: the library as configured against the same
+        # library without the LDS reservation, alternating blocks of 10 launches over the rotating buffers
+        cfg3 = fx.flex_config_default()
+        cfg3.reduce_lds_reserve = 0
+        comm3 = fx.flex_comm_create(N, 0, w_ar.bytes_per_rank, cfg3)
+        ab = {"as_configured": [], "without_reservation": []}
+        for block in range(4):
+            ab["as_configured"] += timed_calls(ar, 10, True)
+            ab["without_reservation"] += timed_calls(
+                lambda k: fx.flex_allreduce_local(comm3, sets[k % nsets][0], sets[k % nsets][1], stream=stream), 10, True)
+        fx.flex_comm_destroy(comm3)
+        extras["reduce_occupancy_cap"] = {
+            "reduce_lds_reserve": int(cfg.reduce_lds_reserve),
+            "allreduce_ms": {k: median(v) for k, v in ab.items()},
+            "allreduce_hbm_GBs": {k: ar_bytes / median(v) / 1e6 for k, v in ab.items()},
+            "launches_each": len(ab["as_configured"])}
         # configuration 2's static split sweep: device-only vs 5 / 12 / 22 % through pinned host memory
         sweep = {}
         for units in (0, 100, 500, 1200, 2200):
