@@ -25,6 +25,10 @@ struct CopyArgs {
     void* dst[FLEX_MAX_RANKS];
     uint64_t bytes[FLEX_MAX_RANKS];
     uint32_t shift;  // only workgroups whose x index is a multiple of 2^shift work
+    // Launch dimensions as plain arguments: a kernel that reads blockDim / gridDim makes the
+    // runtime fill in its hidden launch arguments, which costs 1 us of host time per launch.
+    uint32_t nthreads;  // workgroup size
+    uint32_t nblk;      // working workgroups along x (grid size >> shift)
 };
 
 template <bool NT>
@@ -49,14 +53,14 @@ __global__ void gather_copy_kernel(CopyArgs a) {
     const uint64_t bytes = a.bytes[r];
     if (s == d || bytes == 0) return;  // slice already in place
     // Workgroups go to the 8 accelerator dies round-robin by linear index, and
-    // gridDim.x is a multiple of 2^shift: with shift 3 the working ones all sit
+    // the grid's x size is a multiple of 2^shift: with shift 3 the working ones all sit
     // on one die.
     if (blockIdx.x & ((1u << a.shift) - 1u)) return;
     const uint32_t bid = blockIdx.x >> a.shift;
-    const uint32_t nblk = gridDim.x >> a.shift;
+    const uint32_t nblk = a.nblk;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t nthreads = blockDim.x;
+    const uint32_t nthreads = a.nthreads;
     // body from where the destination reaches a 1 KiB boundary: every wavefront
     // then stores whole, tile-aligned lines (a source at the same offset within
     // 1 KiB, the common case, is aligned there too)
@@ -134,6 +138,8 @@ int launch_gather_copy(const void* const* src, void* const* dst, const uint64_t*
     if (gx == 0) gx = 1;
     a.shift = shape.block_shift > 8 ? 8 : shape.block_shift;
     if (gx > (0x7fffffffull >> a.shift)) gx = 0x7fffffffull >> a.shift;
+    a.nthreads = threads;
+    a.nblk = (uint32_t)gx;
     gx <<= a.shift;
     dim3 grid((uint32_t)gx, (uint32_t)n, 1);
     hipStream_t s = (hipStream_t)stream;

@@ -40,6 +40,10 @@ struct ReduceArgs {
     uint64_t nvec;   // 16-byte vectors in the aligned body
     uint64_t count;  // all elements
     uint32_t shift;  // only workgroups whose index is a multiple of 2^shift work
+    // Launch dimensions as plain arguments: a kernel that reads blockDim / gridDim makes the
+    // runtime fill in its hidden launch arguments, which costs 1 us of host time per launch.
+    uint32_t nthreads;  // workgroup size
+    uint32_t nblk;      // working workgroups (grid size >> shift)
 };
 
 template <bool NT>
@@ -182,12 +186,12 @@ __global__ void reduce_n_kernel(ReduceArgs a) {
     constexpr uint32_t kElemSize = DT == kF32 ? 4 : 2;
     constexpr uint32_t kVecElems = 16 / kElemSize;
     const uint32_t tid = threadIdx.x;
-    const uint32_t nthreads = blockDim.x;
+    const uint32_t nthreads = a.nthreads;
     // Workgroups go to the 8 accelerator dies round-robin by index: with shift 3
     // the working ones all sit on one die.
     if (blockIdx.x & ((1u << a.shift) - 1u)) return;
     const uint32_t bid = blockIdx.x >> a.shift;
-    const uint32_t nblk = gridDim.x >> a.shift;
+    const uint32_t nblk = a.nblk;
     const uint64_t ntiles = (a.nvec + nthreads - 1) / nthreads;  // one vector per thread and tile
 
     const u32x4_in* in[N];
@@ -294,6 +298,8 @@ int launch_reduce_n(const void* const* in, int n, void* out, size_t count, int d
     if (grid == 0) grid = 1;
     a.shift = shape.block_shift > 8 ? 8 : shape.block_shift;
     if (grid > (0x7fffffffull >> a.shift)) grid = 0x7fffffffull >> a.shift;
+    a.nthreads = threads;
+    a.nblk = (uint32_t)grid;
     grid <<= a.shift;
 
     // With one load in flight per wavefront a compute unit that holds its full 32
