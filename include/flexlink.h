@@ -296,7 +296,7 @@ typedef struct flex_config {
                                     4 give 34.7, 6 give 41.9, 8 give 38.2, 16 give 31 GB/s each way) */
     uint32_t sample_every;       /* the Evaluator times every sample_every-th split call (default 1: every call, the
                                     window holds consecutive calls as in the paper); the other split calls fork and
-                                    join with ordering-only events, which saves about 6 us of the 15 us a split call
+                                    join with ordering-only events, which saves about 5 us of the 16 us a split call
                                     costs on top of its kernels.  flex_comm_tune always times every call */
     flex_balancer_cfg_t balancer;
 } flex_config_t;
