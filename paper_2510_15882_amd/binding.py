@@ -273,50 +273,66 @@ def _pointer_array(tensors):
     return arr
 
 
-def _check_tensors(tensors, out):
-    for t in list(tensors) + [out]:
-        if not t.is_cuda or not t.is_contiguous():
+def _marshal(coll, tensors, out, count, require_device=True):
+    """Check the tensors of one collective call and return the array of rank
+    pointers, in one pass (this runs on every call).  The C ABI takes plain
+    pointers and trusts the count: a count beyond a tensor's end would make
+    the kernels read or write outside it, so that is caught here."""
+    n = len(tensors)
+    need_in = count * (n if coll in (FLEX_REDUCESCATTER, FLEX_ALLTOALL) else 1)
+    need_out = count * (n if coll in (FLEX_ALLGATHER, FLEX_ALLTOALL) else 1)
+    dtype = out.dtype
+    if (require_device and not out.is_cuda) or not out.is_contiguous():
+        raise ValueError("tensors must be contiguous CUDA tensors")
+    if count < 0 or out.numel() < need_out:
+        raise ValueError("out holds %d elements, the call writes %d" % (out.numel(), need_out))
+    arr = (ctypes.c_void_p * n)()
+    r = 0
+    for t in tensors:
+        if (require_device and not t.is_cuda) or not t.is_contiguous():
             raise ValueError("tensors must be contiguous CUDA tensors")
-        if t.dtype != out.dtype:
+        if t.dtype != dtype:
             raise ValueError("dtype mismatch")
+        if t.numel() < need_in:
+            raise ValueError("rank %d holds %d elements, the call reads %d" % (r, t.numel(), need_in))
+        arr[r] = t.data_ptr()
+        r += 1
+    return arr
 
 
 def flex_allreduce_local(comm, rank_bufs, out, count=None, op=FLEX_SUM, stream=None):
     """rank_bufs: list of device tensors (one per rank); out: device tensor."""
-    _check_tensors(rank_bufs, out)
     count = rank_bufs[0].numel() if count is None else count
-    _check(lib().flex_allreduce_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
+    _check(lib().flex_allreduce_local(comm, _marshal(FLEX_ALLREDUCE, rank_bufs, out, count), out.data_ptr(), count,
                                       dtype_code(out.dtype), op, _stream_handle(stream)))
 
 
 def flex_allreduce_staged_noalloc(rank_bufs, rank, out, count=None, staged_units=0, op=FLEX_SUM, stream=None):
     """No communicator: the staged part goes through the library's built-in transit buffer."""
-    _check_tensors(rank_bufs, out)
     count = rank_bufs[0].numel() if count is None else count
-    _check(lib().flex_allreduce_staged_noalloc(_pointer_array(rank_bufs), len(rank_bufs), rank, out.data_ptr(), count,
+    _check(lib().flex_allreduce_staged_noalloc(_marshal(FLEX_ALLREDUCE, rank_bufs, out, count), len(rank_bufs), rank, out.data_ptr(), count,
                                                dtype_code(out.dtype), op, staged_units, _stream_handle(stream)))
 
 
 def flex_reducescatter_local(comm, rank_bufs, out, recv_count=None, op=FLEX_SUM, stream=None):
     """rank_bufs: list of nranks device tensors of nranks * recv_count elements."""
-    _check_tensors(rank_bufs, out)
     recv_count = rank_bufs[0].numel() // len(rank_bufs) if recv_count is None else recv_count
-    _check(lib().flex_reducescatter_local(comm, _pointer_array(rank_bufs), out.data_ptr(), recv_count,
+    _check(lib().flex_reducescatter_local(comm, _marshal(FLEX_REDUCESCATTER, rank_bufs, out, recv_count),
+                                          out.data_ptr(), recv_count,
                                           dtype_code(out.dtype), op, _stream_handle(stream)))
 
 
 def flex_allgather_local(comm, rank_slices, out, slice_count=None, stream=None):
-    _check_tensors(rank_slices, out)
     slice_count = rank_slices[0].numel() if slice_count is None else slice_count
-    _check(lib().flex_allgather_local(comm, _pointer_array(rank_slices), out.data_ptr(), slice_count,
+    _check(lib().flex_allgather_local(comm, _marshal(FLEX_ALLGATHER, rank_slices, out, slice_count), out.data_ptr(),
+                                      slice_count,
                                       dtype_code(out.dtype), _stream_handle(stream)))
 
 
 def flex_alltoall_local(comm, rank_bufs, out, count=None, stream=None):
     """rank_bufs: list of nranks device tensors of nranks * count elements."""
-    _check_tensors(rank_bufs, out)
     count = rank_bufs[0].numel() // len(rank_bufs) if count is None else count
-    _check(lib().flex_alltoall_local(comm, _pointer_array(rank_bufs), out.data_ptr(), count,
+    _check(lib().flex_alltoall_local(comm, _marshal(FLEX_ALLTOALL, rank_bufs, out, count), out.data_ptr(), count,
                                      dtype_code(out.dtype), _stream_handle(stream)))
 
 
@@ -325,10 +341,10 @@ def flex_set_split(comm, coll, mode, host_units=0):
 
 
 def flex_comm_tune(comm, coll, rank_bufs, out, count=None, stream=None):
-    _check_tensors(rank_bufs, out)
-    count = rank_bufs[0].numel() if count is None else count
+    if count is None:
+        count = rank_bufs[0].numel() // (len(rank_bufs) if coll in (FLEX_REDUCESCATTER, FLEX_ALLTOALL) else 1)
     res = TuneResult()
-    _check(lib().flex_comm_tune(comm, coll, _pointer_array(rank_bufs), out.data_ptr(), count,
+    _check(lib().flex_comm_tune(comm, coll, _marshal(coll, rank_bufs, out, count), out.data_ptr(), count,
                                 dtype_code(out.dtype), _stream_handle(stream), ctypes.byref(res)))
     return res
 

@@ -303,3 +303,27 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(build, "LIB", str(tmp_path / "libflexlink.so"))
     with pytest.raises(RuntimeError, match="not built"):
         fx.flex_config_default()
+
+
+def test_binding_refuses_counts_beyond_a_tensor():
+    # the C ABI takes plain pointers: the binding is where a count that runs past a
+    # tensor's end can still be caught before a kernel reads or writes outside it
+    import torch
+    n = 4
+    bufs = [torch.zeros(4 * 100) for _ in range(n)]
+    small, big = torch.zeros(100), torch.zeros(4 * 100)
+    fx._marshal(fx.FLEX_ALLREDUCE, bufs, big, 400, require_device=False)
+    fx._marshal(fx.FLEX_REDUCESCATTER, bufs, small, 100, require_device=False)
+    fx._marshal(fx.FLEX_ALLGATHER, [small] * n, big, 100, require_device=False)
+    arr = fx._marshal(fx.FLEX_ALLTOALL, bufs, big, 100, require_device=False)
+    assert [arr[r] for r in range(n)] == [b.data_ptr() for b in bufs]
+    for coll, tensors, out, count in ((fx.FLEX_ALLREDUCE, bufs, big, 401), (fx.FLEX_ALLREDUCE, bufs, small, 400),
+                                      (fx.FLEX_REDUCESCATTER, bufs, small, 101), (fx.FLEX_ALLGATHER, [small] * n, big, 101),
+                                      (fx.FLEX_ALLGATHER, bufs, small, 100), (fx.FLEX_ALLTOALL, bufs, big, 101),
+                                      (fx.FLEX_ALLTOALL, bufs, small, 100), (fx.FLEX_ALLREDUCE, bufs[:3] + [small], big, 400)):
+        with pytest.raises(ValueError):
+            fx._marshal(coll, tensors, out, count, require_device=False)
+    with pytest.raises(ValueError):
+        fx._marshal(fx.FLEX_ALLREDUCE, bufs, big, 400)                     # host tensors
+    with pytest.raises(ValueError):
+        fx._marshal(fx.FLEX_ALLREDUCE, bufs, big.double(), 400, require_device=False)
